@@ -1,0 +1,141 @@
+/*
+ * libasa -- Adaptive Block-Sparse Attention (ASA) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Every tensor pointer is a DEVICE pointer
+ * unless it says HOST.  The caller owns every buffer; the library allocates no device
+ * memory, keeps no state between calls and only borrows pointers until the work it
+ * enqueued on `hip_stream` has completed.  All calls are asynchronous on that stream
+ * (0 / NULL = the default stream); the caller synchronises.
+ *
+ * Method: "BLADE: Block-Sparse Attention Meets Step Distillation for Efficient Video
+ * Generation", Sec. 3.3 (Adaptive Block-Sparse Attention) and appendix "Pseudocode"
+ * (Alg. 1 GetMaxPooledAttnMap, Alg. 2 Compute Block Importance Score, Alg. 3 ASA Mask
+ * Generation).
+ *
+ * Layout.  Q, K, V, O, dO, dQ, dK, dV are bf16 tensors [B, H, L, d] with d contiguous.
+ * Sequence positions are split into Nb = ceil(L / block) blocks of `block` tokens; the
+ * last block may be partial.  A "slab" is one (batch, head) pair, slab index = b*H + h.
+ *
+ * Errors.  Every entry point returns ASA_OK (0) or a negative asa_status.  Arguments are
+ * checked before anything is enqueued, so a failed call writes nothing.  No C++ exception
+ * crosses this boundary.
+ */
+#ifndef ASA_H_
+#define ASA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ASA_VERSION 100
+
+typedef enum asa_status {
+  ASA_OK = 0,
+  ASA_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad parameter, misaligned pointer */
+  ASA_ERR_UNSUPPORTED = -2, /* (block, d) pair or size the kernels were not built for     */
+  ASA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the *_workspace_bytes     */
+  ASA_ERR_HIP = -4          /* a HIP call failed; see asa_last_hip_error()                 */
+} asa_status;
+
+/*
+ * Problem description shared by all entry points.
+ *
+ * Supported: d in {64, 128}; block in {64, 128}; 1 <= L; Nb = ceil(L/block) <= 1024;
+ * 1 <= k_samples <= 16 and k_samples <= block.
+ */
+typedef struct asa_params {
+  int32_t B, H, L, d;
+  int32_t block;                 /* b of Sec. 3.3: query-block size == key-block size        */
+  int32_t k_samples;             /* k of Alg. 2/3: sampled tokens per block (paper: 16)       */
+  const int32_t *sample_offsets; /* HOST pointer to k strictly ascending offsets in [0, b),
+                                    the same for every block, head, Q and K (the sampling of
+                                    Alg. 3 step 3 is drawn by the caller); NULL selects the
+                                    strided default u * (b / k).  Read during the call.      */
+  float tau;                     /* cumulative-score threshold of Alg. 3 step 9              */
+  float r_min, r_max;            /* minimum / maximum retention ratios of Alg. 3 step 9:
+                                    m is clamped to [max(1, ceil(r_min*Nb)),
+                                    max(that, floor(r_max*Nb))]; 0 <= r_min <= r_max <= 1     */
+  int32_t n_prefix_dense;        /* tokens [0, n): every block holding one is always kept as
+                                    a row and as a column (CogVideoX text tokens); 0 = none  */
+  float scale;                   /* soft-max scale; 0 selects 1/sqrt(d)                      */
+  /* Element strides of the B, H and L axes; d has stride 1.  All zero selects the packed
+     layout {H*L*d, L*d, d}.  q_stride also applies to dQ, k_stride to dK, v_stride to dV,
+     o_stride to dO.  Strides must be multiples of 8 elements (16-byte rows).               */
+  int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
+} asa_params;
+
+int asa_version(void);
+const char *asa_error_string(int status); /* static string, never freed                     */
+const char *asa_last_hip_error(void);     /* text of the last HIP failure on this thread    */
+
+/* Workspace sizes in bytes for the calls below (256-byte aligned device memory).           */
+size_t asa_mask_workspace_bytes(const asa_params *p);
+size_t asa_fwd_workspace_bytes(const asa_params *p);
+size_t asa_bwd_workspace_bytes(const asa_params *p);
+
+/*
+ * Mask generation (Sec. 3.3 Steps 1 and 2.1; Alg. 2 -> Alg. 1 -> Alg. 3 steps 6-11).
+ *
+ * From every block of Q and K the k sampled tokens are read; for each sampled query the
+ * soft-max over ALL sampled keys of its slab is formed (online, Alg. 1) and max-pooled to
+ * the block importance map P_imp [Nb, Nb] (fp32).  Each row of P_imp is then ranked by
+ * (score descending, block index ascending); with c_r the fp64 running sum of the r best
+ * scores and T the row total, m* = #{r : c_r < tau*T}; m = clamp(m*, m_min, m_max); the m
+ * best blocks are kept.  Tokens past L take no part.  A NaN score counts as 0.  The
+ * always-kept prefix rows/columns are OR-ed in afterwards.  Every row keeps >= 1 block.
+ *
+ * Outputs (all device):
+ *   mask    [B*H, Nb, Nb] uint8, 1 = keep
+ *   row_ptr [B*H, Nb+1]   int32, offsets into this slab's part of col_idx
+ *   col_idx [B*H, Nb*Nb]  int32, kept key blocks of each row, ascending; entries past
+ *                          row_ptr[Nb] of a slab are left untouched
+ *   col_ptr, row_idx      the same mask by columns (for the backward pass); both NULL to skip
+ *   p_imp   [B*H, Nb, Nb] fp32 importance map, or NULL
+ */
+int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *mask,
+                   int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,
+                   float *p_imp, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The selection rule alone (Alg. 3 steps 6-11) on caller-supplied scores
+ * [B*H, Nb, Nb] fp32 -> mask [B*H, Nb, Nb] uint8 (prefix rows/columns included).
+ */
+int asa_mask_from_scores(const asa_params *p, const float *scores, uint8_t *mask,
+                         void *hip_stream);
+
+/* Index lists of a caller-supplied mask; same layouts as asa_build_mask.                   */
+int asa_csr_from_mask(const asa_params *p, const uint8_t *mask, int32_t *row_ptr,
+                      int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx, void *hip_stream);
+
+/*
+ * Block-sparse attention forward (Sec. 3.3 Step 2.2, standard ASA).  Query block i attends
+ * to the key blocks col_idx[row_ptr[i] .. row_ptr[i+1]) of its slab and to nothing else:
+ *   S = scale * Q_i K_j^T (keys >= L excluded),  LSE = log sum exp S,  O = exp(S - LSE) V.
+ * o   [B, H, L, d] bf16 (o_stride); rows >= L do not exist and nothing is written there
+ * lse [B*H, L] fp32, natural logarithm; a row with an empty list gets O = 0, LSE = -inf
+ * bf16 products accumulate in fp32; probabilities are rounded to bf16 before P V.
+ */
+int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *v,
+                 const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Block-sparse attention backward with the mask held constant (the mask restricts
+ * attention "during both training and inference", Sec. 3.3 Step 2.1).  With
+ * P = exp(S - LSE), Delta = rowsum(dO * O), dS = P * (dO V^T - Delta):
+ *   dV = P^T dO,  dK = scale * dS^T Q,  dQ = scale * dS K     over the kept tiles only.
+ * o, lse are the forward's outputs; col_ptr/row_idx is the mask by columns.
+ * dq, dk, dv [B, H, L, d] bf16 (q/k/v strides); every row < L is written.
+ */
+int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
+                 const void *d_o, const float *lse, const int32_t *row_ptr,
+                 const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
+                 void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASA_H_ */

@@ -1,0 +1,215 @@
+// C-ABI entry points of libasa: argument checks, defaults, workspace carving, launches.
+#include <math.h>
+#include <string.h>
+
+#include "asa_common.hpp"
+
+namespace asa {
+
+static thread_local char g_hip_error[256] = "";
+
+void set_hip_error(hipError_t e) {
+  const char *s = hipGetErrorString(e);
+  strncpy(g_hip_error, s ? s : "unknown HIP error", sizeof(g_hip_error) - 1);
+  g_hip_error[sizeof(g_hip_error) - 1] = 0;
+}
+
+static bool view_from(const int64_t st[3], const Problem &pb, TensorView *tv) {
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
+    tv->sL = pb.d;
+    tv->sH = (int64_t)pb.L * pb.d;
+    tv->sB = (int64_t)pb.H * pb.L * pb.d;
+    return true;
+  }
+  if (st[2] < pb.d || st[0] < 0 || st[1] < 0) return false;
+  if ((st[0] % 8) || (st[1] % 8) || (st[2] % 8)) return false;  // rows are read 16 bytes at a time
+  tv->sB = st[0];
+  tv->sH = st[1];
+  tv->sL = st[2];
+  return true;
+}
+
+int resolve(const asa_params *p, Problem *o) {
+  if (!p || !o) return ASA_ERR_INVALID_ARG;
+  if (p->B < 1 || p->H < 1 || p->L < 1) return ASA_ERR_INVALID_ARG;
+  if ((int64_t)p->B * p->H > 65535) return ASA_ERR_UNSUPPORTED;
+  if (p->d != 64 && p->d != 128) return ASA_ERR_UNSUPPORTED;
+  if (p->block != 64 && p->block != 128) return ASA_ERR_UNSUPPORTED;
+  memset(o, 0, sizeof(*o));
+  o->B = p->B; o->H = p->H; o->L = p->L; o->d = p->d; o->block = p->block;
+  o->Nb = (p->L + p->block - 1) / p->block;
+  if (o->Nb > kMaxNb) return ASA_ERR_UNSUPPORTED;
+  o->Lpad = o->Nb * p->block;
+  o->n_slabs = p->B * p->H;
+  // sampling (Alg. 2 steps 1-3): k offsets inside a block, shared by every block
+  if (p->k_samples < 1 || p->k_samples > p->block) return ASA_ERR_INVALID_ARG;
+  if (p->k_samples > kMaxSamples) return ASA_ERR_UNSUPPORTED;
+  o->ks = p->k_samples;
+  for (int u = 0; u < o->ks; ++u) {
+    int off = p->sample_offsets ? p->sample_offsets[u] : u * (p->block / p->k_samples);
+    if (off < 0 || off >= p->block) return ASA_ERR_INVALID_ARG;
+    if (u && off <= o->offs[u - 1]) return ASA_ERR_INVALID_ARG;
+    o->offs[u] = off;
+  }
+  // rule parameters (Alg. 3 step 9)
+  if (p->tau != p->tau) return ASA_ERR_INVALID_ARG;
+  if (!(p->r_min >= 0.f) || !(p->r_max <= 1.f) || !(p->r_min <= p->r_max)) return ASA_ERR_INVALID_ARG;
+  o->tau = p->tau;
+  int lo = (int)ceil((double)p->r_min * (double)o->Nb);
+  if (lo < 1) lo = 1;
+  if (lo > o->Nb) lo = o->Nb;
+  int hi = (int)floor((double)p->r_max * (double)o->Nb);
+  if (hi < lo) hi = lo;
+  if (hi > o->Nb) hi = o->Nb;
+  o->m_min = lo;
+  o->m_max = hi;
+  if (p->n_prefix_dense < 0 || p->n_prefix_dense > p->L) return ASA_ERR_INVALID_ARG;
+  o->n_prefix_blocks = (p->n_prefix_dense + p->block - 1) / p->block;
+  if (p->scale != p->scale || p->scale < 0.f || isinf(p->scale)) return ASA_ERR_INVALID_ARG;
+  o->scale = p->scale == 0.f ? 1.0f / sqrtf((float)p->d) : p->scale;
+  if (!view_from(p->q_stride, *o, &o->q) || !view_from(p->k_stride, *o, &o->k) ||
+      !view_from(p->v_stride, *o, &o->v) || !view_from(p->o_stride, *o, &o->o))
+    return ASA_ERR_INVALID_ARG;
+  return ASA_OK;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+static bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t transposed_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.d * pb.Lpad * sizeof(uint16_t));
+}
+
+static int finish(hipError_t e) {
+  if (e == hipSuccess) return ASA_OK;
+  set_hip_error(e);
+  return ASA_ERR_HIP;
+}
+
+}  // namespace asa
+
+using namespace asa;
+
+extern "C" {
+
+int asa_version(void) { return ASA_VERSION; }
+
+const char *asa_error_string(int status) {
+  switch (status) {
+    case ASA_OK: return "ok";
+    case ASA_ERR_INVALID_ARG: return "invalid argument";
+    case ASA_ERR_UNSUPPORTED: return "unsupported size or (block, d) combination";
+    case ASA_ERR_WORKSPACE: return "workspace missing or too small";
+    case ASA_ERR_HIP: return "HIP runtime error (see asa_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+const char *asa_last_hip_error(void) { return g_hip_error; }
+
+size_t asa_mask_workspace_bytes(const asa_params *p) {
+  Problem pb;
+  if (resolve(p, &pb) != ASA_OK) return 0;
+  // importance map when the caller does not ask for it
+  return round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
+}
+
+size_t asa_fwd_workspace_bytes(const asa_params *p) {
+  Problem pb;
+  if (resolve(p, &pb) != ASA_OK) return 0;
+  return transposed_bytes(pb);  // V as [slab][d][Lpad]
+}
+
+size_t asa_bwd_workspace_bytes(const asa_params *p) {
+  Problem pb;
+  if (resolve(p, &pb) != ASA_OK) return 0;
+  return bwd_workspace_bytes(pb);
+}
+
+int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *mask,
+                   int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,
+                   float *p_imp, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!q || !k || !mask || !row_ptr || !col_idx) return ASA_ERR_INVALID_ARG;
+  if ((col_ptr == nullptr) != (row_idx == nullptr)) return ASA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned4(row_ptr) || !aligned4(col_idx) ||
+      !aligned4(col_ptr) || !aligned4(row_idx) || !aligned4(p_imp))
+    return ASA_ERR_INVALID_ARG;
+  float *scores = p_imp;
+  if (!scores) {
+    if (!workspace || workspace_bytes < asa_mask_workspace_bytes(p) || !aligned16(workspace))
+      return ASA_ERR_WORKSPACE;
+    scores = reinterpret_cast<float *>(workspace);
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = launch_probe(pb, q, k, scores, st);
+  if (e != hipSuccess) return finish(e);
+  e = launch_rule(pb, scores, mask, st);
+  if (e != hipSuccess) return finish(e);
+  return finish(launch_csr(pb, mask, row_ptr, col_idx, col_ptr, row_idx, st));
+}
+
+int asa_mask_from_scores(const asa_params *p, const float *scores, uint8_t *mask,
+                         void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!scores || !mask || !aligned4(scores)) return ASA_ERR_INVALID_ARG;
+  return finish(launch_rule(pb, scores, mask, reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
+int asa_csr_from_mask(const asa_params *p, const uint8_t *mask, int32_t *row_ptr,
+                      int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!mask || !row_ptr || !col_idx) return ASA_ERR_INVALID_ARG;
+  if ((col_ptr == nullptr) != (row_idx == nullptr)) return ASA_ERR_INVALID_ARG;
+  if (!aligned4(row_ptr) || !aligned4(col_idx) || !aligned4(col_ptr) || !aligned4(row_idx))
+    return ASA_ERR_INVALID_ARG;
+  return finish(launch_csr(pb, mask, row_ptr, col_idx, col_ptr, row_idx,
+                           reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
+int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *v,
+                 const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
+                 void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!q || !k || !v || !row_ptr || !col_idx || !o || !lse) return ASA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned4(lse) ||
+      !aligned4(row_ptr) || !aligned4(col_idx))
+    return ASA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < transposed_bytes(pb) || !aligned16(workspace))
+    return ASA_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = launch_transpose(pb, v, pb.v, workspace, st);
+  if (e != hipSuccess) return finish(e);
+  return finish(launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, lse, st));
+}
+
+int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
+                 const void *d_o, const float *lse, const int32_t *row_ptr,
+                 const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
+                 void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!q || !k || !v || !o || !d_o || !lse || !row_ptr || !col_idx || !col_ptr || !row_idx ||
+      !dq || !dk || !dv)
+    return ASA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
+      !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned4(lse) ||
+      !aligned4(row_ptr) || !aligned4(col_idx) || !aligned4(col_ptr) || !aligned4(row_idx))
+    return ASA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < bwd_workspace_bytes(pb) || !aligned16(workspace))
+    return ASA_ERR_WORKSPACE;
+  return finish(launch_bwd(pb, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
+                           dv, workspace, reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Shared declarations of the libasa translation units (host side + device helpers).
+// gfx950 only: 64-wide wavefronts, bf16 MFMA 32x32x16 / 16x16x32.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "asa.h"
+
+namespace asa {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int kMaxNb = 1024;
+constexpr int kMaxSamples = 16;
+constexpr int kNumXcd = 8;
+
+// A [B, H, L, d] bf16 tensor seen from the device: element strides of B, H, L.
+struct TensorView {
+  int64_t sB, sH, sL;
+};
+
+// Parameters after validation and defaulting; passed by value to kernels.
+struct Problem {
+  int B, H, L, d, block;
+  int Nb;        // ceil(L / block)
+  int Lpad;      // Nb * block
+  int n_slabs;   // B * H
+  int ks;        // samples per block
+  int n_prefix_blocks;
+  int m_min, m_max;
+  float tau;
+  float scale;
+  TensorView q, k, v, o;
+  int offs[kMaxSamples];
+};
+
+int resolve(const asa_params *p, Problem *out);  // asa_status
+void set_hip_error(hipError_t e);
+
+// launchers (each returns a hipError_t from the launch)
+hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView &tv, void *dst,
+                            hipStream_t st);
+hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
+                      const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
+                      hipStream_t st);
+hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
+                      int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
+hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
+                        hipStream_t st);
+hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);
+hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const void *v,
+                      const void *o, const void *d_o, const float *lse, const int32_t *row_ptr,
+                      const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx,
+                      void *dq, void *dk, void *dv, void *workspace, hipStream_t st);
+size_t bwd_workspace_bytes(const Problem &pb);
+
+#ifdef __HIPCC__
+// ---------------------------------------------------------------- device helpers
+
+__device__ __forceinline__ const bf16 *slab_ptr(const void *base, const TensorView &tv, int slab,
+                                                int H) {
+  int b = slab / H, h = slab - b * H;
+  return reinterpret_cast<const bf16 *>(base) + (int64_t)b * tv.sB + (int64_t)h * tv.sH;
+}
+__device__ __forceinline__ bf16 *slab_ptr(void *base, const TensorView &tv, int slab, int H) {
+  int b = slab / H, h = slab - b * H;
+  return reinterpret_cast<bf16 *>(base) + (int64_t)b * tv.sB + (int64_t)h * tv.sH;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by their linear id.  Give each XCD one
+// contiguous range of work items, so that the workgroups sharing an L2 work on the same slab.
+__device__ __forceinline__ int xcd_contiguous_work(int wg, int total) {
+  int chunk = (total + kNumXcd - 1) / kNumXcd;
+  int w = (wg % kNumXcd) * chunk + wg / kNumXcd;
+  return (wg / kNumXcd < chunk && w < total) ? w : -1;
+}
+inline int xcd_grid(int total) { return ((total + kNumXcd - 1) / kNumXcd) * kNumXcd; }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return *reinterpret_cast<uint32_t *>(&r);
+}
+
+// value of the other 32-lane half of the wavefront
+__device__ __forceinline__ float swap_halves(float x) { return __shfl_xor(x, 32, 64); }
+#endif
+
+}  // namespace asa

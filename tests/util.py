@@ -1,0 +1,47 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+
+import numpy as np
+import torch
+
+from paper_2508_10774_amd import binding, synth
+
+O_MAX_ABS = 2e-2      # max-abs tolerance on O, dQ, dK, dV for bf16 inputs
+O_MEAN_ABS = 2e-3     # mean-abs tolerance
+LSE_ABS = 1e-3
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bits -> torch.bfloat16 tensor on the GPU (same bits)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.view(torch.bfloat16).cuda()
+
+
+def host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def lists_from_mask(p: binding.Params, mask_np: np.ndarray, with_csc=True):
+    """Upload a [S, Nb, Nb] uint8 mask and build its index lists with the library."""
+    bufs = binding.alloc_index_lists(p, with_csc=with_csc)
+    bufs["mask"].copy_(torch.from_numpy(np.ascontiguousarray(mask_np.reshape(bufs["mask"].shape))))
+    binding.asa_csr_from_mask(p, bufs["mask"], bufs["row_ptr"], bufs["col_idx"],
+                              bufs.get("col_ptr"), bufs.get("row_idx"))
+    return bufs
+
+
+def run_fwd(p: binding.Params, q, k, v, bufs):
+    o = torch.empty((p.B, p.H, p.L, p.d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((p.B * p.H, p.L), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(binding.asa_fwd_workspace_bytes(p))
+    binding.asa_attn_fwd(p, q, k, v, bufs["row_ptr"], bufs["col_idx"], o, lse, ws)
+    torch.cuda.synchronize()
+    return o, lse
+
+
+def assert_close_bf16(got: np.ndarray, want: np.ndarray, what: str,
+                      max_abs=O_MAX_ABS, mean_abs=O_MEAN_ABS):
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    assert err.max() <= max_abs, f"{what}: max-abs {err.max():.3e} > {max_abs}"
+    assert err.mean() <= mean_abs, f"{what}: mean-abs {err.mean():.3e} > {mean_abs}"
+    return float(err.max()), float(err.mean())
