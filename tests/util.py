@@ -45,3 +45,53 @@ def assert_close_bf16(got: np.ndarray, want: np.ndarray, what: str,
     assert err.max() <= max_abs, f"{what}: max-abs {err.max():.3e} > {max_abs}"
     assert err.mean() <= mean_abs, f"{what}: mean-abs {err.mean():.3e} > {mean_abs}"
     return float(err.max()), float(err.mean())
+
+
+# ---------------------------------------------------------------------------
+# mask parity accounting
+# ---------------------------------------------------------------------------
+
+SCORE_GAP = 1e-6   # normalised-score gap below which a mask disagreement is excused
+
+
+def classify_mask_rows(P, mask_o, mask_g, tau, gap=SCORE_GAP):
+    """Compare GPU and oracle masks row by row (no forced prefix in either).
+
+    P: oracle importance map [..., Nb] fp32.  A row whose masks differ is *excused* only if
+    the difference is explained by oracle scores that are closer than `gap` (normalised by
+    the row sum): (a) a different m needs every cumulative normalised score between the two
+    m's to lie within `gap` of tau; (b) blocks swapped at equal m need normalised scores
+    within `gap` of each other.  Returns (exact, excused, failed) row counts and the list of
+    failed rows.
+    """
+    Nb = P.shape[-1]
+    P2 = np.nan_to_num(P.reshape(-1, Nb).astype(np.float64), nan=0.0)
+    mo = mask_o.reshape(-1, Nb).astype(bool)
+    mg = mask_g.reshape(-1, Nb).astype(bool)
+    t32 = float(np.float32(tau))
+    exact = excused = 0
+    failed = []
+    for r in np.nonzero((mo != mg).any(axis=1))[0]:
+        w = P2[r]
+        T = w.sum() or 1.0
+        order = np.lexsort((np.arange(Nb), -w))
+        s = w[order] / T
+        cum = np.concatenate([[0.0], np.cumsum(s)])
+        m_o, m_g = int(mo[r].sum()), int(mg[r].sum())
+        ok = True
+        if m_o != m_g:
+            lo, hi = sorted((m_o, m_g))
+            ok = all(abs(cum[x] - t32) < gap for x in range(lo, hi))
+        if ok:
+            top_g = np.zeros(Nb, bool)
+            top_g[order[:m_g]] = True
+            diff = np.nonzero(top_g != mg[r])[0]
+            if len(diff):
+                sc = w[diff] / T
+                ok = (sc.max() - sc.min()) < gap
+        if ok:
+            excused += 1
+        else:
+            failed.append(int(r))
+    exact = mo.shape[0] - excused - len(failed)
+    return exact, excused, failed
