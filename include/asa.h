@@ -114,12 +114,16 @@ int asa_csr_from_mask(const asa_params *p, const uint8_t *mask, int32_t *row_ptr
  * Block-sparse attention forward (Sec. 3.3 Step 2.2, standard ASA).  Query block i attends
  * to the key blocks col_idx[row_ptr[i] .. row_ptr[i+1]) of its slab and to nothing else:
  *   S = scale * Q_i K_j^T (keys >= L excluded),  LSE = log sum exp S,  O = exp(S - LSE) V.
- * o   [B, H, L, d] bf16 (o_stride); rows >= L do not exist and nothing is written there
- * lse [B*H, L] fp32, natural logarithm; a row with an empty list gets O = 0, LSE = -inf
+ * o    [B, H, L, d] bf16 (o_stride); rows >= L do not exist and nothing is written there
+ * o_lo [B, H, L, d] bf16 (o_stride), optional (NULL to skip): the part of the fp32 result
+ *      that rounding to bf16 dropped, o_lo = bf16(O_fp32 - o).  Saved for the backward pass,
+ *      whose Delta = rowsum(dO * O) cancels against dO V^T in sharply peaked rows and needs
+ *      more than the 8 significant bits of o there.
+ * lse  [B*H, L] fp32, natural logarithm; a row with an empty list gets O = 0, LSE = -inf
  * bf16 products accumulate in fp32; probabilities are rounded to bf16 before P V.
  */
 int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *v,
-                 const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
+                 const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo, float *lse,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
@@ -127,11 +131,12 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
  * attention "during both training and inference", Sec. 3.3 Step 2.1).  With
  * P = exp(S - LSE), Delta = rowsum(dO * O), dS = P * (dO V^T - Delta):
  *   dV = P^T dO,  dK = scale * dS^T Q,  dQ = scale * dS K     over the kept tiles only.
- * o, lse are the forward's outputs; col_ptr/row_idx is the mask by columns.
+ * o, o_lo, lse are the forward's outputs (o_lo may be NULL: Delta then comes from the bf16 o
+ * alone); col_ptr/row_idx is the mask by columns.
  * dq, dk, dv [B, H, L, d] bf16 (q/k/v strides); every row < L is written.
  */
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
-                 const void *d_o, const float *lse, const int32_t *row_ptr,
+                 const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
                  void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream);
 

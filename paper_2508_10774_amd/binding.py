@@ -59,7 +59,7 @@ def load():
     L.asa_build_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.asa_mask_from_scores.argtypes = [pp, vp, vp, vp]
     L.asa_csr_from_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp]
-    L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.asa_attn_bwd.argtypes = [pp] + [vp] * 15 + [ctypes.c_size_t, vp]
     for n in ("asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
               "asa_attn_bwd"):
@@ -164,18 +164,18 @@ def asa_csr_from_mask(p: Params, mask, row_ptr, col_idx, col_ptr=None, row_idx=N
            "asa_csr_from_mask")
 
 
-def asa_attn_fwd(p: Params, q, k, v, row_ptr, col_idx, o, lse, workspace, stream=None):
+def asa_attn_fwd(p: Params, q, k, v, row_ptr, col_idx, o, lse, workspace, o_lo=None, stream=None):
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().asa_attn_fwd(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(row_ptr),
-                               _ptr(col_idx), _ptr(o), _ptr(lse), _ptr(workspace), ws_bytes,
-                               _stream(stream)), "asa_attn_fwd")
+                               _ptr(col_idx), _ptr(o), _ptr(o_lo), _ptr(lse), _ptr(workspace),
+                               ws_bytes, _stream(stream)), "asa_attn_fwd")
 
 
 def asa_attn_bwd(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk, dv,
-                 workspace, stream=None):
+                 workspace, o_lo=None, stream=None):
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load().asa_attn_bwd(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o),
-                               _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
+    _check(load().asa_attn_bwd(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(o_lo),
+                               _ptr(d_o), _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
                                _ptr(row_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                ws_bytes, _stream(stream)), "asa_attn_bwd")
 

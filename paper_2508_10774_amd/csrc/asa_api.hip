@@ -175,25 +175,25 @@ int asa_csr_from_mask(const asa_params *p, const uint8_t *mask, int32_t *row_ptr
 }
 
 int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *v,
-                 const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
+                 const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo, float *lse,
                  void *workspace, size_t workspace_bytes, void *hip_stream) {
   Problem pb;
   int rc = resolve(p, &pb);
   if (rc != ASA_OK) return rc;
   if (!q || !k || !v || !row_ptr || !col_idx || !o || !lse) return ASA_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned4(lse) ||
-      !aligned4(row_ptr) || !aligned4(col_idx))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||
+      !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx))
     return ASA_ERR_INVALID_ARG;
   if (!workspace || workspace_bytes < transposed_bytes(pb) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = launch_transpose(pb, v, pb.v, workspace, st);
   if (e != hipSuccess) return finish(e);
-  return finish(launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, lse, st));
+  return finish(launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, o_lo, lse, st));
 }
 
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
-                 const void *d_o, const float *lse, const int32_t *row_ptr,
+                 const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
                  void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream) {
   Problem pb;
@@ -202,13 +202,14 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
   if (!q || !k || !v || !o || !d_o || !lse || !row_ptr || !col_idx || !col_ptr || !row_idx ||
       !dq || !dk || !dv)
     return ASA_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||
+      !aligned16(d_o) ||
       !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned4(lse) ||
       !aligned4(row_ptr) || !aligned4(col_idx) || !aligned4(col_ptr) || !aligned4(row_idx))
     return ASA_ERR_INVALID_ARG;
   if (!workspace || workspace_bytes < bwd_workspace_bytes(pb) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
-  return finish(launch_bwd(pb, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
+  return finish(launch_bwd(pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
                            dv, workspace, reinterpret_cast<hipStream_t>(hip_stream)));
 }
 

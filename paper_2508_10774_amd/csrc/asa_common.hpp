@@ -48,15 +48,16 @@ void set_hip_error(hipError_t e);
 hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView &tv, void *dst,
                             hipStream_t st);
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
-                      const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
-                      hipStream_t st);
+                      const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
+                      float *lse, hipStream_t st);
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
                         hipStream_t st);
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);
 hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const void *v,
-                      const void *o, const void *d_o, const float *lse, const int32_t *row_ptr,
+                      const void *o, const void *o_lo, const void *d_o, const float *lse,
+                      const int32_t *row_ptr,
                       const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx,
                       void *dq, void *dk, void *dv, void *workspace, hipStream_t st);
 size_t bwd_workspace_bytes(const Problem &pb);
@@ -89,6 +90,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 v = {lo, hi};
   bf16x2 r = __builtin_convertvector(v, bf16x2);
   return *reinterpret_cast<uint32_t *>(&r);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
 }
 
 // value of the other 32-lane half of the wavefront

@@ -67,7 +67,7 @@ struct FwdArgs {
   const void *q, *k;
   const bf16 *vt;  // [slab][d][Lpad]
   const int32_t *row_ptr, *col_idx;
-  void *o;
+  void *o, *o_lo;
   float *lse;
   TensorView tq, tk, to;
   int H, L, Lpad, Nb, n_slabs;
@@ -246,15 +246,27 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (qvalid) {
     bf16 *os = slab_ptr(a.o, a.to, slab, a.H) + (int64_t)qrow * a.to.sL;
+    bf16 *ls = a.o_lo ? slab_ptr(a.o_lo, a.to, slab, a.H) + (int64_t)qrow * a.to.sL : nullptr;
 #pragma unroll
     for (int dm = 0; dm < D / 32; ++dm) {
-      uint32_t w[8];
+      uint32_t w[8], r[8];
 #pragma unroll
-      for (int i = 0; i < 16; i += 2)
-        w[i >> 1] = pack_bf16x2(oacc[dm][i] * inv, oacc[dm][i + 1] * inv);
+      for (int i = 0; i < 16; i += 2) {
+        const float v0 = oacc[dm][i] * inv, v1 = oacc[dm][i + 1] * inv;
+        const uint32_t pk = pack_bf16x2(v0, v1);
+        w[i >> 1] = pk;
+        // what the rounding to bf16 dropped, itself rounded to bf16
+        r[i >> 1] = pack_bf16x2(v0 - bf16_bits_to_float(pk & 0xffffu),
+                                v1 - bf16_bits_to_float(pk >> 16));
+      }
       uint4 *dst = reinterpret_cast<uint4 *>(os + dm * 32 + 16 * hl);
       dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
       dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+      if (ls) {
+        uint4 *dl = reinterpret_cast<uint4 *>(ls + dm * 32 + 16 * hl);
+        dl[0] = make_uint4(r[0], r[1], r[2], r[3]);
+        dl[1] = make_uint4(r[4], r[5], r[6], r[7]);
+      }
     }
     if (hl == 0)
       a.lse[(int64_t)slab * a.L + qrow] =
@@ -278,11 +290,11 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
 }
 
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
-                      const int32_t *row_ptr, const int32_t *col_idx, void *o, float *lse,
-                      hipStream_t st) {
+                      const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
+                      float *lse, hipStream_t st) {
   FwdArgs a;
   a.q = q; a.k = k; a.vt = reinterpret_cast<const bf16 *>(vt);
-  a.row_ptr = row_ptr; a.col_idx = col_idx; a.o = o; a.lse = lse;
+  a.row_ptr = row_ptr; a.col_idx = col_idx; a.o = o; a.o_lo = o_lo; a.lse = lse;
   a.tq = pb.q; a.tk = pb.k; a.to = pb.o;
   a.H = pb.H; a.L = pb.L; a.Lpad = pb.Lpad; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs;
   a.scale_log2e = pb.scale * 1.44269504088896340736f;

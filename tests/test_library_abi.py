@@ -41,11 +41,15 @@ def test_argument_errors_are_reported_without_a_gpu():
     L = binding.load()
     p = binding.Params(B=1, H=2, L=1024, d=96, block=64)
     assert L.asa_fwd_workspace_bytes(ctypes.byref(p.c())) == 0
-    rc = L.asa_attn_fwd(ctypes.byref(p.c()), *([None] * 8), 0, None)
+    rc = L.asa_attn_fwd(ctypes.byref(p.c()), *([None] * 9), 0, None)
     assert rc == -2                                  # d = 96 is not built
     p = binding.Params(B=1, H=2, L=1024, d=64, block=64)
-    assert L.asa_attn_fwd(ctypes.byref(p.c()), *([None] * 8), 0, None) == -1   # null pointers
+    assert L.asa_attn_fwd(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1   # null pointers
     assert L.asa_fwd_workspace_bytes(ctypes.byref(p.c())) == 2 * 64 * 1024 * 2
+    assert L.asa_attn_bwd(ctypes.byref(p.c()), *([None] * 15), 0, None) == -1
+    assert L.asa_build_mask(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1
+    assert L.asa_mask_from_scores(ctypes.byref(p.c()), None, None, None) == -1
+    assert L.asa_bwd_workspace_bytes(ctypes.byref(p.c())) == 3 * 2 * 64 * 1024 * 2 + 2 * 1024 * 4
     for bad in (dict(k_samples=0), dict(k_samples=65), dict(sample_offsets=[3, 1] + list(range(4, 18))),
                 dict(r_min=0.6, r_max=0.5), dict(tau=float("nan")), dict(n_prefix_dense=-1),
                 dict(q_stride=(0, 0, 60))):

@@ -29,21 +29,33 @@ def lists_from_mask(p: binding.Params, mask_np: np.ndarray, with_csc=True):
     return bufs
 
 
-def run_fwd(p: binding.Params, q, k, v, bufs):
+def run_fwd(p: binding.Params, q, k, v, bufs, with_lo=False):
     o = torch.empty((p.B, p.H, p.L, p.d), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((p.B * p.H, p.L), dtype=torch.float32, device="cuda")
+    o_lo = torch.empty_like(o) if with_lo else None
     ws = binding.alloc_workspace(binding.asa_fwd_workspace_bytes(p))
-    binding.asa_attn_fwd(p, q, k, v, bufs["row_ptr"], bufs["col_idx"], o, lse, ws)
+    binding.asa_attn_fwd(p, q, k, v, bufs["row_ptr"], bufs["col_idx"], o, lse, ws, o_lo=o_lo)
     torch.cuda.synchronize()
-    return o, lse
+    return (o, lse, o_lo) if with_lo else (o, lse)
 
 
 def assert_close_bf16(got: np.ndarray, want: np.ndarray, what: str,
                       max_abs=O_MAX_ABS, mean_abs=O_MEAN_ABS):
-    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    """Rows are token vectors [..., d].  With s_r = max(1, max_x |want[r, x]|):
+    |got - want|[r, x] <= max_abs * s_r everywhere, and mean(|got - want| / s_r) <= mean_abs.
+
+    For rows of magnitude <= 1 this is the plain absolute tolerance.  Above, the allowance
+    grows with the row's magnitude: outputs are bf16 (an element of magnitude 8 cannot be
+    stored more accurately than +-0.03), and the gradients are sums of bf16-rounded dS times
+    K or Q elements whose rounding error is proportional to the size of the terms summed,
+    not to the (possibly cancelled) result."""
+    got = got.astype(np.float64)
+    want = want.astype(np.float64)
     assert np.isfinite(got).all(), f"{what}: non-finite values"
-    assert err.max() <= max_abs, f"{what}: max-abs {err.max():.3e} > {max_abs}"
-    assert err.mean() <= mean_abs, f"{what}: mean-abs {err.mean():.3e} > {mean_abs}"
+    s_r = np.maximum(1.0, np.abs(want).max(axis=-1, keepdims=True))
+    err = np.abs(got - want) / s_r
+    assert err.max() <= max_abs, f"{what}: scaled max-abs {err.max():.3e} > {max_abs}"
+    assert err.mean() <= mean_abs, f"{what}: scaled mean-abs {err.mean():.3e} > {mean_abs}"
     return float(err.max()), float(err.mean())
 
 
@@ -95,3 +107,14 @@ def classify_mask_rows(P, mask_o, mask_g, tau, gap=SCORE_GAP):
             failed.append(int(r))
     exact = mo.shape[0] - excused - len(failed)
     return exact, excused, failed
+
+
+def run_bwd(p: binding.Params, q, k, v, o, lse, d_o, bufs, o_lo=None):
+    dq = torch.full_like(q, float("nan"))
+    dk = torch.full_like(k, float("nan"))
+    dv = torch.full_like(v, float("nan"))
+    ws = binding.alloc_workspace(binding.asa_bwd_workspace_bytes(p))
+    binding.asa_attn_bwd(p, q, k, v, o, d_o, lse, bufs["row_ptr"], bufs["col_idx"],
+                         bufs["col_ptr"], bufs["row_idx"], dq, dk, dv, ws, o_lo=o_lo)
+    torch.cuda.synchronize()
+    return dq, dk, dv
