@@ -140,6 +140,16 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
                  void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Profiling hook for benchmarks.  Arms the calling thread so that the NEXT asa_attn_fwd,
+ * asa_attn_bwd or asa_build_mask call records `start_event` immediately before and
+ * `stop_event` immediately after its dominant kernel(s) -- the tile loop of the forward, the
+ * dK/dV and dQ kernels of the backward, the probe of the mask build -- on the call's stream,
+ * leaving out the small preparation kernels around them.  Both are hipEvent_t handles owned by
+ * the caller.  One shot: the hook disarms itself when used; pass NULL, NULL to disarm.
+ */
+int asa_set_kernel_timing(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,7 +37,8 @@ class asa_params(ctypes.Structure):
 
 EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_workspace_bytes",
            "asa_fwd_workspace_bytes", "asa_bwd_workspace_bytes", "asa_build_mask",
-           "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd", "asa_attn_bwd"]
+           "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd", "asa_attn_bwd",
+           "asa_set_kernel_timing"]
 
 
 def load():
@@ -61,8 +62,9 @@ def load():
     L.asa_csr_from_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.asa_attn_bwd.argtypes = [pp] + [vp] * 15 + [ctypes.c_size_t, vp]
+    L.asa_set_kernel_timing.argtypes = [vp, vp]
     for n in ("asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
-              "asa_attn_bwd"):
+              "asa_attn_bwd", "asa_set_kernel_timing"):
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -178,6 +180,14 @@ def asa_attn_bwd(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row
                                _ptr(d_o), _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
                                _ptr(row_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                ws_bytes, _stream(stream)), "asa_attn_bwd")
+
+
+def asa_set_kernel_timing(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):
+    """Arm the one-shot hook with two torch events (they must have been recorded once, which
+    is what creates their HIP handles)."""
+    a = ctypes.c_void_p(start.cuda_event) if start is not None else None
+    b = ctypes.c_void_p(stop.cuda_event) if stop is not None else None
+    _check(load().asa_set_kernel_timing(a, b), "asa_set_kernel_timing")
 
 
 # ---------------------------------------------------------------------------

@@ -14,6 +14,17 @@ void set_hip_error(hipError_t e) {
   g_hip_error[sizeof(g_hip_error) - 1] = 0;
 }
 
+static thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
+void timing_begin(hipStream_t st) {
+  if (g_ev_start) (void)hipEventRecord(g_ev_start, st);
+}
+void timing_end(hipStream_t st) {
+  if (g_ev_stop) (void)hipEventRecord(g_ev_stop, st);
+  g_ev_start = nullptr;
+  g_ev_stop = nullptr;
+}
+
 static bool view_from(const int64_t st[3], const Problem &pb, TensorView *tv) {
   if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
     tv->sL = pb.d;
@@ -108,6 +119,13 @@ const char *asa_error_string(int status) {
 
 const char *asa_last_hip_error(void) { return g_hip_error; }
 
+int asa_set_kernel_timing(void *start_event, void *stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return ASA_ERR_INVALID_ARG;
+  g_ev_start = reinterpret_cast<hipEvent_t>(start_event);
+  g_ev_stop = reinterpret_cast<hipEvent_t>(stop_event);
+  return ASA_OK;
+}
+
 size_t asa_mask_workspace_bytes(const asa_params *p) {
   Problem pb;
   if (resolve(p, &pb) != ASA_OK) return 0;
@@ -145,7 +163,9 @@ int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *m
     scores = reinterpret_cast<float *>(workspace);
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  timing_begin(st);
   hipError_t e = launch_probe(pb, q, k, scores, st);
+  timing_end(st);
   if (e != hipSuccess) return finish(e);
   e = launch_rule(pb, scores, mask, st);
   if (e != hipSuccess) return finish(e);
@@ -189,7 +209,10 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = launch_transpose(pb, v, pb.v, workspace, st);
   if (e != hipSuccess) return finish(e);
-  return finish(launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, o_lo, lse, st));
+  timing_begin(st);
+  e = launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, o_lo, lse, st);
+  timing_end(st);
+  return finish(e);
 }
 
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,

@@ -385,11 +385,15 @@ static hipError_t launch_bwd_t(const BwdArgs &a, hipStream_t st) {
     attr_set = true;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
+  timing_begin(st);
   hipLaunchKernelGGL((dkv_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDkvLds, st, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((dq_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
-  return hipGetLastError();
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((dq_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
+    e = hipGetLastError();
+  }
+  timing_end(st);
+  return e;
 }
 
 hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const void *v,

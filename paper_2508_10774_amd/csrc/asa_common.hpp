@@ -44,6 +44,11 @@ struct Problem {
 int resolve(const asa_params *p, Problem *out);  // asa_status
 void set_hip_error(hipError_t e);
 
+// One-shot profiling hook (asa_set_kernel_timing): record the armed events around the dominant
+// kernel of a call.  timing_begin / timing_end are no-ops when nothing is armed.
+void timing_begin(hipStream_t st);
+void timing_end(hipStream_t st);
+
 // launchers (each returns a hipError_t from the launch)
 hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView &tv, void *dst,
                             hipStream_t st);
