@@ -10,10 +10,10 @@
 // Operand orientation (32x32x16 bf16 MFMA, see asa_fwd.hip for kappa / rho):
 //   dq_kernel : keys on the M axis, queries on lanes: S^T = K Q^T and dP^T = V dO^T share the
 //               accumulator layout, LSE and Delta are per-lane scalars, and bf16(dS^T) is directly
-//               the B operand of dQ^T = K^T dS^T (K^T tiles come from a [d][L] copy of K).
+//               the B operand of dQ^T = K^T dS^T (K^T tiles come from a per-block transposed copy of K).
 //   dkv_kernel: queries on the M axis, keys on lanes: S = Q K^T, dP = dO V^T with K, V of the
 //               wave's 32 keys resident in registers; bf16(P) and bf16(dS) are the B operands of
-//               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T tiles from [d][L] copies).
+//               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T tiles from per-block transposed copies).
 #include "asa_common.hpp"
 
 namespace asa {
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *o, const void *o
 
 struct BwdArgs {
   const void *q, *k, *v, *d_o;
-  const bf16 *qt, *kt, *dot;  // [slab][d][Lpad] copies of Q, K, dO
+  const bf16 *qt, *kt, *dot;  // [slab][Nb][d][block] transposed-tile copies of Q, K, dO
   const float *lse, *delta;
   const int32_t *row_ptr, *col_idx, *col_ptr, *row_idx;
   void *dq, *dk, *dv;
@@ -102,16 +102,16 @@ __device__ __forceinline__ void load_row_tile(bf16 *dst, const bf16 *src, int64_
     *reinterpret_cast<uint4 *>(dst + r * (D + 8) + cc * 8) = val;
   }
 }
-// copy a [D][BLK] tile of a [d][Lpad] array into LDS
+// copy transposed tile `blk` ([D][BLK], contiguous) of a [Nb][d][block] array into LDS
 template <int BLK, int D, int THREADS>
-__device__ __forceinline__ void load_col_tile(bf16 *dst, const bf16 *src, int Lpad, int col0,
-                                              int tid) {
+__device__ __forceinline__ void load_col_tile(bf16 *dst, const bf16 *src, int blk, int tid) {
   constexpr int CV = BLK / 8;
+  const bf16 *tile = src + (int64_t)blk * D * BLK;
 #pragma unroll
   for (int i = 0; i < D * CV / THREADS; ++i) {
     int c = tid + i * THREADS;
     int r = c / CV, cc = c % CV;
-    uint4 val = *reinterpret_cast<const uint4 *>(src + (int64_t)r * Lpad + col0 + cc * 8);
+    uint4 val = *reinterpret_cast<const uint4 *>(tile + c * 8);
     *reinterpret_cast<uint4 *>(dst + r * (BLK + 8) + cc * 8) = val;
   }
 }
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
     __syncthreads();
     load_row_tile<BLK, D, C::kThreads>(Ks, ks, a.tk.sL, j * BLK, a.L, tid);
     load_row_tile<BLK, D, C::kThreads>(Vs, vs, a.tv.sL, j * BLK, a.L, tid);
-    load_col_tile<BLK, D, C::kThreads>(Kt, kts, a.Lpad, j * BLK, tid);
+    load_col_tile<BLK, D, C::kThreads>(Kt, kts, j, tid);
     __syncthreads();
     const bool tail = j * BLK + BLK > a.L;
 #pragma unroll
@@ -280,8 +280,8 @@ __global__ __launch_bounds__(BLK * 2, 1) void dkv_kernel(BwdArgs a) {
     __syncthreads();
     load_row_tile<BLK, D, C::kThreads>(Qs, qs, a.tq.sL, i_blk * BLK, a.L, tid);
     load_row_tile<BLK, D, C::kThreads>(Gs, gs, a.to.sL, i_blk * BLK, a.L, tid);
-    load_col_tile<BLK, D, C::kThreads>(Qt, qts, a.Lpad, i_blk * BLK, tid);
-    load_col_tile<BLK, D, C::kThreads>(Gt, gts, a.Lpad, i_blk * BLK, tid);
+    load_col_tile<BLK, D, C::kThreads>(Qt, qts, i_blk, tid);
+    load_col_tile<BLK, D, C::kThreads>(Gt, gts, i_blk, tid);
     if (tid < BLK) {
       int r = i_blk * BLK + tid;
       bool ok = r < a.L;
@@ -367,7 +367,7 @@ static size_t transposed_bytes(const Problem &pb) {
 }
 
 size_t bwd_workspace_bytes(const Problem &pb) {
-  // Q^T, K^T, dO^T as [slab][d][Lpad] bf16, then Delta [slab][L] fp32
+  // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32
   return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float));
 }
 

@@ -16,11 +16,14 @@
 namespace asa {
 
 // ---------------------------------------------------------------------------------------
-// [slab][L][d] -> [slab][d][Lpad] bf16 transpose, zero-filled for positions >= L.
+// [slab][L][d] -> [slab][Nb][d][block] bf16: every block of `block` positions becomes one
+// contiguous transposed tile (channels major), zero-filled for positions >= L.  A tile is then
+// a single contiguous run in memory for the attention kernels, instead of d rows that are
+// Lpad * 2 bytes apart (a power-of-two pitch that lands every row on the same memory channel).
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void transpose_kernel(const void *src, TensorView tv, int H,
-                                                        int L, int Lpad, bf16 *dst) {
+                                                        int L, int Lpad, int block, bf16 *dst) {
   constexpr int TL = 64;  // positions per workgroup
   __shared__ uint16_t tile[TL][D + 2];
   const int slab = blockIdx.y;
@@ -37,14 +40,16 @@ __global__ __launch_bounds__(256) void transpose_kernel(const void *src, TensorV
     for (int x = 0; x < 8; ++x) tile[r][cc * 8 + x] = e[x];
   }
   __syncthreads();
-  uint16_t *out = reinterpret_cast<uint16_t *>(dst) + (int64_t)slab * D * Lpad;
+  // the 64 positions of this workgroup lie inside one block (block is a multiple of 64)
+  uint16_t *out = reinterpret_cast<uint16_t *>(dst) + (int64_t)slab * D * Lpad +
+                  (int64_t)(l0 / block) * D * block + (l0 % block);
   for (int c = tid; c < D * (TL / 8); c += 256) {
     int dd = c / (TL / 8), lc = c % (TL / 8);
     uint4 val;
     uint16_t *e = reinterpret_cast<uint16_t *>(&val);
 #pragma unroll
     for (int x = 0; x < 8; ++x) e[x] = tile[lc * 8 + x][dd];
-    *reinterpret_cast<uint4 *>(out + (int64_t)dd * Lpad + l0 + lc * 8) = val;
+    *reinterpret_cast<uint4 *>(out + (int64_t)dd * block + lc * 8) = val;
   }
 }
 
@@ -53,10 +58,10 @@ hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView
   dim3 grid(pb.Lpad / 64, pb.n_slabs);
   if (pb.d == 128)
     hipLaunchKernelGGL(transpose_kernel<128>, grid, dim3(256), 0, st, src, tv, pb.H, pb.L, pb.Lpad,
-                       reinterpret_cast<bf16 *>(dst));
+                       pb.block, reinterpret_cast<bf16 *>(dst));
   else
     hipLaunchKernelGGL(transpose_kernel<64>, grid, dim3(256), 0, st, src, tv, pb.H, pb.L, pb.Lpad,
-                       reinterpret_cast<bf16 *>(dst));
+                       pb.block, reinterpret_cast<bf16 *>(dst));
   return hipGetLastError();
 }
 
@@ -65,7 +70,7 @@ hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView
 // ---------------------------------------------------------------------------------------
 struct FwdArgs {
   const void *q, *k;
-  const bf16 *vt;  // [slab][d][Lpad]
+  const bf16 *vt;  // [slab][Nb][d][block]: V, one transposed tile per key block
   const int32_t *row_ptr, *col_idx;
   void *o, *o_lo;
   float *lse;
@@ -167,7 +172,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
         int cidx = tid + i * C::kThreads;
         int r = cidx / CV, cc = cidx % CV;
         uint4 val =
-            *reinterpret_cast<const uint4 *>(vts + (int64_t)r * a.Lpad + j * BLK + cc * 8);
+            *reinterpret_cast<const uint4 *>(vts + ((int64_t)j * D + r) * BLK + cc * 8);
         *reinterpret_cast<uint4 *>(Vs + r * C::kVStride + cc * 8) = val;
       }
     }

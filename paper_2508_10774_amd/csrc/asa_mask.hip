@@ -9,18 +9,23 @@ namespace asa {
 // Probe: P_imp[i][j] = max over sampled rows of block i and sampled keys of block j of the
 // soft-max (over ALL sampled keys of the slab) of scale * Qs Ks^T.
 //
-// One wavefront per query block, following Alg. 1: a first sweep over the key blocks keeps
-// per sampled query the running maximum Mt, the running denominator lt and the per-block row
-// maximum Rt[j] (LDS); a second sweep turns Rt into probabilities and max-pools over rows.
-// The sampled rows are gathered straight from Q and K (Alg. 2 steps 1-3): a 16 x 16 logit
-// tile is one chain of 16x16x32 bf16 MFMAs with the keys on the M axis, so a lane holds
-// 4 keys of one sampled query.
+// Alg. 1 of the paper, reorganised for 64-wide wavefronts.  One wavefront owns TWO query
+// blocks and sweeps the key blocks two at a time: one chain of 32x32x16 bf16 MFMAs gives the
+// 32 x 32 logit tile (2 key blocks x 16 samples on the M axis, 2 query blocks x 16 samples
+// on the N axis).  The rows of the A operand are ordered so that lane half h holds, for ONE
+// sampled query, all 16 samples of key block j0 + h: the block-row maximum Rt[query][j] of
+// Alg. 1 is then a lane-local maximum, and the running maximum / denominator of the row is
+// kept lane-locally over the key blocks of that parity and merged across the two halves once,
+// at the end.  No cross-lane traffic inside the sweep.  The sampled rows are gathered straight
+// from Q and K (Alg. 2 steps 1-3); the next pair of key blocks is fetched while the current
+// one is being reduced.  A second sweep turns Rt into probabilities and max-pools over rows.
 // ---------------------------------------------------------------------------------------
 struct ProbeArgs {
   const void *q, *k;
   float *p_imp;
   TensorView tq, tk;
   int H, L, Nb, n_slabs, block, ks;
+  int n_valid_last;  // sampled tokens of the last block that lie below L
   float scale;
   int offs[kMaxSamples];
 };
@@ -28,106 +33,120 @@ struct ProbeArgs {
 template <int D>
 __global__ __launch_bounds__(64) void probe_kernel(ProbeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float *Rt = reinterpret_cast<float *>(smem);  // [Nb][16]
-  __shared__ float sM[16];
-  __shared__ double sL[16];
+  float *Rt = reinterpret_cast<float *>(smem);  // [2 * ceil(Nb / 2)][32]
+  __shared__ float sM[32];
+  __shared__ double sL[32];
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  const int n_pairs = (a.Nb + 1) / 2;
+  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * n_pairs);
   if (work < 0) return;
-  const int slab = work / a.Nb;
-  const int i = work - slab * a.Nb;
+  const int slab = work / n_pairs;
+  const int i0 = (work - slab * n_pairs) * 2;
   const int lane = threadIdx.x;
-  const int g = lane >> 4;   // key group: keys 4g .. 4g+3 of a tile live in this lane
-  const int n = lane & 15;   // sampled query (B column) / sampled key (A row)
+  const int hl = lane >> 5;  // operand k-half on loads, key-block parity on results
+  const int n = lane & 31;   // A row on loads; query column on results
 
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
 
-  // offset of sample slot n inside a block; slots >= ks do not exist
-  int my_off = 0;
-#pragma unroll
-  for (int u = 0; u < kMaxSamples; ++u)
-    if (u == n) my_off = a.offs[u];
-  const bool slot_ok = n < a.ks;
-
-  // B operand: sampled query n of block i, channels 32s + 8g .. +8
-  const int qpos = i * a.block + my_off;
-  const bool q_ok = slot_ok && qpos < a.L;
-  bf16x8 qreg[D / 32];
-  {
-    const int qp = q_ok ? qpos : 0;
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s)
-      qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + (int64_t)qp * a.tq.sL + 32 * s + 8 * g);
-  }
-  // offsets of the 4 keys whose logits land in this lane (rows 4g .. 4g+3 of the tile)
-  int koff[4];
-  bool kslot[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    int u = 4 * g + r;
-    kslot[r] = u < a.ks;
+  auto offset_of = [&](int u) {
     int o = 0;
 #pragma unroll
-    for (int uu = 0; uu < kMaxSamples; ++uu)
-      if (uu == u) o = a.offs[uu];
-    koff[r] = o;
-  }
+    for (int x = 0; x < kMaxSamples; ++x)
+      if (x == u) o = a.offs[x];
+    return o;
+  };
+  auto valid_in_block = [&](int blk) {
+    return blk >= a.Nb ? 0 : (blk == a.Nb - 1 ? a.n_valid_last : a.ks);
+  };
 
-  float Mt = -INFINITY;  // running maximum of my query (replicated over the 4 key groups)
-  double lt = 0.0;       // running denominator
-
-  for (int j = 0; j < a.Nb; ++j) {
-    // A operand: sampled key n of block j
-    const int kpos = j * a.block + my_off;
-    const int kp = (slot_ok && kpos < a.L) ? kpos : 0;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  // B operand: column n = sampled query (n & 15) of query block i0 + (n >> 4)
+  const int q_blk = i0 + (n >> 4);
+  const int q_slot = n & 15;
+  const bool q_ok = q_slot < valid_in_block(q_blk);
+  bf16x8 qreg[D / 16];
+  {
+    const int64_t qpos = q_ok ? (int64_t)q_blk * a.block + offset_of(q_slot) : 0;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-      bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + (int64_t)kp * a.tk.sL + 32 * s + 8 * g);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[s], acc, 0, 0, 0);
-    }
-    float sv[4];
+    for (int s = 0; s < D / 16; ++s)
+      qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + qpos * a.tq.sL + 16 * s + 8 * hl);
+  }
+  // A operand: row r = 8g + 4h + j is sample 4g + j of key block j0 + h
+  const int k_par = (n >> 2) & 1;
+  const int k_slot = 4 * (n >> 3) + (n & 3);
+  const int k_off = offset_of(k_slot);
+  auto load_keys = [&](int j0, bf16x8 *dst) {
+    const int blk = j0 + k_par;
+    const int64_t kpos = k_slot < valid_in_block(blk) ? (int64_t)blk * a.block + k_off : 0;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      dst[s] = *reinterpret_cast<const bf16x8 *>(ks + kpos * a.tk.sL + 16 * s + 8 * hl);
+  };
+
+  float Mt = -INFINITY;  // running maximum of my query over the key blocks of parity hl
+  double lt = 0.0;       // running denominator over the same keys
+
+  bf16x8 kcur[D / 16], knext[D / 16];
+  load_keys(0, kcur);
+  for (int j0 = 0; j0 < a.Nb; j0 += 2) {
+    if (j0 + 2 < a.Nb) load_keys(j0 + 2, knext);
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kcur[s], qreg[s], acc, 0, 0, 0);
+    // register i of lane half hl is sample i of key block j0 + hl
+    const int nv = valid_in_block(j0 + hl);
+    float sv[16];
     float mij = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      bool ok = kslot[r] && (j * a.block + koff[r] < a.L);
-      sv[r] = ok ? acc[r] * a.scale : -INFINITY;
-      mij = fmaxf(mij, sv[r]);
+    for (int i = 0; i < 16; ++i) {
+      sv[i] = i < nv ? acc[i] * a.scale : -INFINITY;
+      mij = fmaxf(mij, sv[i]);
     }
-    mij = fmaxf(mij, __shfl_xor(mij, 16, 64));
-    mij = fmaxf(mij, __shfl_xor(mij, 32, 64));
-    if (g == 0) Rt[j * 16 + n] = mij;
-    // a tile without a valid key (mij = -inf) must leave the running pair untouched
-    const float mij_s = (mij == -INFINITY) ? 0.f : mij;
-    float lij = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) lij += __expf(sv[r] - mij_s);
-    lij += __shfl_xor(lij, 16, 64);
-    lij += __shfl_xor(lij, 32, 64);
+    Rt[(j0 + hl) * 32 + n] = mij;
     const float mnew = fmaxf(Mt, mij);
     const float mnew_s = (mnew == -INFINITY) ? 0.f : mnew;
-    lt = (double)__expf(Mt - mnew_s) * lt + (double)__expf(mij - mnew_s) * (double)lij;
+    float lij = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lij += __expf(sv[i] - mnew_s);
+    lt = (double)__expf(Mt - mnew_s) * lt + (double)lij;
     Mt = mnew;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) kcur[s] = knext[s];
   }
-  if (g == 0) {
-    sM[n] = Mt;
-    sL[n] = lt;
+  // merge the two parities of each query
+  {
+    const float Mo = __shfl_xor(Mt, 32, 64);
+    const double lo = __shfl_xor(lt, 32, 64);
+    const float Mall = fmaxf(Mt, Mo);
+    const float Ms = (Mall == -INFINITY) ? 0.f : Mall;
+    const double lall = (double)__expf(Mt - Ms) * lt + (double)__expf(Mo - Ms) * lo;
+    if (hl == 0) {
+      sM[n] = Mall;
+      sL[n] = lall;
+    }
   }
   __syncthreads();
 
-  float *out = a.p_imp + ((int64_t)slab * a.Nb + i) * a.Nb;
-  for (int j = lane; j < a.Nb; j += 64) {
-    float best = 0.f;
-    for (int u = 0; u < a.ks; ++u) {
-      const bool row_ok = i * a.block + a.offs[u] < a.L;
-      const float rt = Rt[j * 16 + u];
-      if (row_ok && rt != -INFINITY) {
-        float pr = (float)((double)__expf(rt - sM[u]) / sL[u]);
-        best = fmaxf(best, pr);
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int i = i0 + qb;
+    if (i >= a.Nb) break;
+    const int rows_ok = valid_in_block(i);
+    float *out = a.p_imp + ((int64_t)slab * a.Nb + i) * a.Nb;
+    for (int j = lane; j < a.Nb; j += 64) {
+      float best = 0.f;
+      for (int u = 0; u < rows_ok; ++u) {
+        const float rt = Rt[j * 32 + qb * 16 + u];
+        if (rt != -INFINITY) {
+          float pr = (float)((double)__expf(rt - sM[qb * 16 + u]) / sL[qb * 16 + u]);
+          best = fmaxf(best, pr);
+        }
       }
+      out[j] = best;
     }
-    out[j] = best;
   }
 }
 
@@ -138,8 +157,12 @@ hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *
   a.H = pb.H; a.L = pb.L; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs; a.block = pb.block; a.ks = pb.ks;
   a.scale = pb.scale;
   for (int u = 0; u < kMaxSamples; ++u) a.offs[u] = pb.offs[u];
-  const int grid = xcd_grid(pb.n_slabs * pb.Nb);
-  const size_t lds = (size_t)pb.Nb * 16 * sizeof(float);
+  a.n_valid_last = 0;
+  for (int u = 0; u < pb.ks; ++u)
+    if ((int64_t)(pb.Nb - 1) * pb.block + pb.offs[u] < pb.L) ++a.n_valid_last;
+  const int n_pairs = (pb.Nb + 1) / 2;
+  const int grid = xcd_grid(pb.n_slabs * n_pairs);
+  const size_t lds = (size_t)n_pairs * 2 * 32 * sizeof(float);
   if (pb.d == 128)
     hipLaunchKernelGGL(probe_kernel<128>, dim3(grid), dim3(64), lds, st, a);
   else
@@ -229,6 +252,9 @@ hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hi
 
 // ---------------------------------------------------------------------------------------
 // Index lists.  blockIdx.x = slab, blockIdx.y = 0: by rows (CSR), 1: by columns (CSC).
+// Both walk the mask row by row so that every load is coalesced: the CSR side gives a
+// wavefront one row at a time (64 columns per step, positions from a ballot), the CSC side
+// gives every thread one column.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void csr_kernel(const uint8_t *mask, int Nb, int32_t *row_ptr,
                                                   int32_t *col_idx, int32_t *col_ptr,
@@ -240,13 +266,25 @@ __global__ __launch_bounds__(256) void csr_kernel(const uint8_t *mask, int Nb, i
   if (ptr == nullptr) return;
   const int slab = blockIdx.x;
   const uint8_t *m = mask + (int64_t)slab * Nb * Nb;
-  const int64_t s_major = by_col ? 1 : Nb;  // step between lists
-  const int64_t s_minor = by_col ? Nb : 1;  // step inside a list
-  const int tid = threadIdx.x;
-  for (int r = tid; r < Nb; r += 256) {
-    int c = 0;
-    for (int x = 0; x < Nb; ++x) c += m[r * s_major + x * s_minor] != 0;
-    cnt[r] = c;
+  ptr += (int64_t)slab * (Nb + 1);
+  idx += (int64_t)slab * Nb * Nb;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+  if (by_col) {
+    for (int c = tid; c < Nb; c += 256) {
+      int n = 0;
+      for (int r = 0; r < Nb; ++r) n += m[(int64_t)r * Nb + c] != 0;
+      cnt[c] = n;
+    }
+  } else {
+    for (int r = wave; r < Nb; r += 4) {
+      int n = 0;
+      for (int c0 = 0; c0 < Nb; c0 += 64) {
+        const bool f = (c0 + lane < Nb) && m[(int64_t)r * Nb + c0 + lane] != 0;
+        n += __popcll(__ballot(f));
+      }
+      if (lane == 0) cnt[r] = n;
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -259,13 +297,23 @@ __global__ __launch_bounds__(256) void csr_kernel(const uint8_t *mask, int Nb, i
     cnt[Nb] = run;
   }
   __syncthreads();
-  ptr += (int64_t)slab * (Nb + 1);
-  idx += (int64_t)slab * Nb * Nb;
   for (int r = tid; r <= Nb; r += 256) ptr[r] = cnt[r];
-  for (int r = tid; r < Nb; r += 256) {
-    int o = cnt[r];
-    for (int x = 0; x < Nb; ++x)
-      if (m[r * s_major + x * s_minor] != 0) idx[o++] = x;
+  if (by_col) {
+    for (int c = tid; c < Nb; c += 256) {
+      int o = cnt[c];
+      for (int r = 0; r < Nb; ++r)
+        if (m[(int64_t)r * Nb + c] != 0) idx[o++] = r;
+    }
+  } else {
+    for (int r = wave; r < Nb; r += 4) {
+      int o = cnt[r];
+      for (int c0 = 0; c0 < Nb; c0 += 64) {
+        const bool f = (c0 + lane < Nb) && m[(int64_t)r * Nb + c0 + lane] != 0;
+        const unsigned long long b = __ballot(f);
+        if (f) idx[o + __popcll(b & ((1ull << lane) - 1ull))] = c0 + lane;
+        o += __popcll(b);
+      }
+    }
   }
 }
 
