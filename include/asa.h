@@ -94,6 +94,8 @@ size_t asa_bwd_workspace_bytes(const asa_params *p);
  *                          row_ptr[Nb] of a slab are left untouched
  *   col_ptr, row_idx      the same mask by columns (for the backward pass); both NULL to skip
  *   p_imp   [B*H, Nb, Nb] fp32 importance map, or NULL
+ * The workspace (asa_mask_workspace_bytes) is always needed: it holds the probe's per-row
+ * block maxima and, when p_imp is NULL, the importance map.
  */
 int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *mask,
                    int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,

@@ -129,8 +129,9 @@ int asa_set_kernel_timing(void *start_event, void *stop_event) {
 size_t asa_mask_workspace_bytes(const asa_params *p) {
   Problem pb;
   if (resolve(p, &pb) != ASA_OK) return 0;
-  // importance map when the caller does not ask for it
-  return round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
+  // the probe's per-row block maxima, then the importance map (used when the caller does not
+  // ask for it)
+  return probe_workspace_bytes(pb) + round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
 }
 
 size_t asa_fwd_workspace_bytes(const asa_params *p) {
@@ -156,15 +157,14 @@ int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *m
   if (!aligned16(q) || !aligned16(k) || !aligned4(row_ptr) || !aligned4(col_idx) ||
       !aligned4(col_ptr) || !aligned4(row_idx) || !aligned4(p_imp))
     return ASA_ERR_INVALID_ARG;
-  float *scores = p_imp;
-  if (!scores) {
-    if (!workspace || workspace_bytes < asa_mask_workspace_bytes(p) || !aligned16(workspace))
-      return ASA_ERR_WORKSPACE;
-    scores = reinterpret_cast<float *>(workspace);
-  }
+  if (!workspace || workspace_bytes < asa_mask_workspace_bytes(p) || !aligned16(workspace))
+    return ASA_ERR_WORKSPACE;
+  float *scores = p_imp ? p_imp
+                        : reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(workspace) +
+                                                    probe_workspace_bytes(pb));
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   timing_begin(st);
-  hipError_t e = launch_probe(pb, q, k, scores, st);
+  hipError_t e = launch_probe(pb, q, k, scores, workspace, st);
   timing_end(st);
   if (e != hipSuccess) return finish(e);
   e = launch_rule(pb, scores, mask, st);

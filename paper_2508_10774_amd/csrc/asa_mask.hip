@@ -9,20 +9,26 @@ namespace asa {
 // Probe: P_imp[i][j] = max over sampled rows of block i and sampled keys of block j of the
 // soft-max (over ALL sampled keys of the slab) of scale * Qs Ks^T.
 //
-// Alg. 1 of the paper, reorganised for 64-wide wavefronts.  One wavefront owns TWO query
-// blocks and sweeps the key blocks two at a time: one chain of 32x32x16 bf16 MFMAs gives the
-// 32 x 32 logit tile (2 key blocks x 16 samples on the M axis, 2 query blocks x 16 samples
-// on the N axis).  The rows of the A operand are ordered so that lane half h holds, for ONE
-// sampled query, all 16 samples of key block j0 + h: the block-row maximum Rt[query][j] of
-// Alg. 1 is then a lane-local maximum, and the running maximum / denominator of the row is
-// kept lane-locally over the key blocks of that parity and merged across the two halves once,
-// at the end.  No cross-lane traffic inside the sweep.  The sampled rows are gathered straight
-// from Q and K (Alg. 2 steps 1-3); the next pair of key blocks is fetched while the current
-// one is being reduced.  A second sweep turns Rt into probabilities and max-pools over rows.
+// Alg. 1 of the paper, reorganised for 64-wide wavefronts.  A workgroup of 8 wavefronts owns 8
+// query blocks and sweeps the key blocks of its slab: wavefronts w and w + 4 share two query
+// blocks and split every chunk of key blocks between them.  The sampled key rows (Alg. 2
+// steps 1-3) are gathered from K by direct global->LDS loads, 8 key blocks (128 rows) per
+// chunk, double-buffered and shared by all wavefronts.  One chain of 32x32x16
+// bf16 MFMAs gives a 32 x 32 logit tile: 2 key blocks x 16 samples on the M axis, 2 query
+// blocks x 16 samples on the N axis.  The rows of the A operand are ordered so that lane half h
+// holds, for ONE sampled query, all 16 samples of key block j0 + h: the block-row maximum
+// Rt[query][j] of Alg. 1 is then a lane-local maximum, and the running maximum / denominator of
+// the row is kept lane-locally over the key blocks of that parity and merged across the two
+// halves (and the two wavefronts of a pair) once, at the end.  No cross-lane traffic inside the
+// sweep; the exponentials of a tile depend only on that tile's own maximum (Alg. 1 steps 12-14),
+// so consecutive tiles overlap.  Rt goes to a workspace in
+// global memory (it stays in L2); a second sweep turns it into probabilities and max-pools
+// over the sampled rows.
 // ---------------------------------------------------------------------------------------
 struct ProbeArgs {
   const void *q, *k;
   float *p_imp;
+  float *rt;         // workspace [work item][wave][Nb rounded up to 8][32]
   TensorView tq, tk;
   int H, L, Nb, n_slabs, block, ks;
   int n_valid_last;  // sampled tokens of the last block that lie below L
@@ -30,21 +36,48 @@ struct ProbeArgs {
   int offs[kMaxSamples];
 };
 
-template <int D>
-__global__ __launch_bounds__(64) void probe_kernel(ProbeArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  float *Rt = reinterpret_cast<float *>(smem);  // [2 * ceil(Nb / 2)][32]
-  __shared__ float sM[32];
-  __shared__ double sL[32];
+constexpr int kProbeQBlocks = 8;   // query blocks per workgroup
+constexpr int kProbeKBlocks = 8;   // key blocks per LDS chunk
 
-  const int n_pairs = (a.Nb + 1) / 2;
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * n_pairs);
+typedef __attribute__((address_space(3))) void lds_void_m;
+__device__ __forceinline__ void probe_dma16(const void *src, void *lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, (lds_void_m *)lds_dst, 16, 0, 0);
+#endif
+}
+
+// chunk-position swizzle of the sampled-key rows in LDS (16 rows read together differ in row
+// bits 0..2 and 4; at D = 64 a row is half the banks and parity picks the half)
+template <int D>
+__device__ __forceinline__ int probe_swz(int row) {
+  return D == 128 ? ((row & 7) | (((row >> 4) & 1) << 3)) : (((row >> 1) & 3) | (((row >> 4) & 1) << 2));
+}
+
+template <int D>
+__global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
+  constexpr int ROWS = kProbeKBlocks * 16;          // sampled rows per chunk
+  constexpr int CH = D / 8;                         // 16-byte chunks per row
+  constexpr int DMA_PER_WAVE = ROWS * CH / 64 / 8;  // 1 KB per wave instruction, 8 wavefronts
+  extern __shared__ __align__(1024) unsigned char probe_smem[];
+  bf16 (*Kc)[ROWS * D] = reinterpret_cast<bf16 (*)[ROWS * D]>(probe_smem);   // two buffers
+  __shared__ float sM[8][32];    // per wavefront: running maximum of its share of the keys
+  __shared__ double sL[8][32];   //                and the matching denominator
+
+  const int n_groups = (a.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
+  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * n_groups);
   if (work < 0) return;
-  const int slab = work / n_pairs;
-  const int i0 = (work - slab * n_pairs) * 2;
-  const int lane = threadIdx.x;
+  const int slab = work / n_groups;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int pair = wave & 3;      // which two query blocks
+  const int half = wave >> 2;     // which half of every chunk of key blocks
+  const int i_base = (work - slab * n_groups) * kProbeQBlocks;
+  const int i0 = i_base + 2 * pair;
   const int hl = lane >> 5;  // operand k-half on loads, key-block parity on results
   const int n = lane & 31;   // A row on loads; query column on results
+  const int nb_pad = (a.Nb + kProbeKBlocks - 1) / kProbeKBlocks * kProbeKBlocks;
+  float *rt = a.rt + ((int64_t)work * 4 + pair) * nb_pad * 32;
 
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
@@ -62,59 +95,88 @@ __global__ __launch_bounds__(64) void probe_kernel(ProbeArgs a) {
 
   // B operand: column n = sampled query (n & 15) of query block i0 + (n >> 4)
   const int q_blk = i0 + (n >> 4);
-  const int q_slot = n & 15;
-  const bool q_ok = q_slot < valid_in_block(q_blk);
+  const bool q_ok = (n & 15) < valid_in_block(q_blk);
   bf16x8 qreg[D / 16];
   {
-    const int64_t qpos = q_ok ? (int64_t)q_blk * a.block + offset_of(q_slot) : 0;
+    const int64_t qpos = q_ok ? (int64_t)q_blk * a.block + offset_of(n & 15) : 0;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + qpos * a.tq.sL + 16 * s + 8 * hl);
   }
-  // A operand: row r = 8g + 4h + j is sample 4g + j of key block j0 + h
-  const int k_par = (n >> 2) & 1;
-  const int k_slot = 4 * (n >> 3) + (n & 3);
-  const int k_off = offset_of(k_slot);
-  auto load_keys = [&](int j0, bf16x8 *dst) {
-    const int blk = j0 + k_par;
-    const int64_t kpos = k_slot < valid_in_block(blk) ? (int64_t)blk * a.block + k_off : 0;
+
+  // producer: my share of a chunk of sampled key rows (row r of a chunk = key block r / 16,
+  // sample r % 16)
+  int dma_tok[DMA_PER_WAVE];   // token offset inside the chunk, or -1 for a sample slot >= ks
+  int dma_pos[DMA_PER_WAVE];   // swizzled 16-byte position to fetch
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-      dst[s] = *reinterpret_cast<const bf16x8 *>(ks + kpos * a.tk.sL + 16 * s + 8 * hl);
+  for (int i = 0; i < DMA_PER_WAVE; ++i) {
+    const int seg = wave * DMA_PER_WAVE + i;
+    const int row = seg * (64 / CH) + lane / CH;
+    dma_tok[i] = (row / 16) * a.block + offset_of(row % 16);
+    dma_pos[i] = ((lane % CH) ^ probe_swz<D>(row)) * 8;
+  }
+  auto fetch = [&](int chunk, int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+      const int seg = wave * DMA_PER_WAVE + i;
+      int64_t tok = (int64_t)chunk * kProbeKBlocks * a.block + dma_tok[i];
+      tok = tok < a.L ? tok : 0;   // padded samples: any valid row, masked out below
+      probe_dma16(ks + tok * a.tk.sL + dma_pos[i], &Kc[buf][seg * 512]);
+    }
   };
+
+  // consumer: A row r = 8g + 4h + j is sample 4g + j of key block j0 + h
+  const int a_row = ((n >> 2) & 1) * 16 + 4 * (n >> 3) + (n & 3);   // row inside a pair of key blocks
+  const int a_swz = probe_swz<D>(a_row);
 
   float Mt = -INFINITY;  // running maximum of my query over the key blocks of parity hl
   double lt = 0.0;       // running denominator over the same keys
 
-  bf16x8 kcur[D / 16], knext[D / 16];
-  load_keys(0, kcur);
-  for (int j0 = 0; j0 < a.Nb; j0 += 2) {
-    if (j0 + 2 < a.Nb) load_keys(j0 + 2, knext);
-    f32x16 acc;
+  const int n_chunks = nb_pad / kProbeKBlocks;
+  fetch(0, 0);
+  for (int chunk = 0; chunk < n_chunks; ++chunk) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): my loads of this chunk have landed
+    __syncthreads();                     // everyone's have, and the other buffer is free
+    if (chunk + 1 < n_chunks) fetch(chunk + 1, (chunk + 1) & 1);
+    const bf16 *Kb = Kc[chunk & 1];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int sb = 0; sb < kProbeKBlocks / 4; ++sb) {
+      const int sub = half * (kProbeKBlocks / 4) + sb;
+      const int j0 = chunk * kProbeKBlocks + 2 * sub;
+      const bf16 *rp = Kb + (sub * 32 + a_row) * D;
+      f32x16 acc;
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kcur[s], qreg[s], acc, 0, 0, 0);
-    // register i of lane half hl is sample i of key block j0 + hl
-    const int nv = valid_in_block(j0 + hl);
-    float sv[16];
-    float mij = -INFINITY;
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      sv[i] = i < nv ? acc[i] * a.scale : -INFINITY;
-      mij = fmaxf(mij, sv[i]);
+      for (int s = 0; s < D / 16; ++s) {
+        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * s + hl) ^ a_swz) * 8));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc, 0, 0, 0);
+      }
+      // register i of lane half hl is sample i of key block j0 + hl; samples past L (only in
+      // the last block), past the last block, or in sample slots >= k are masked out
+      if (a.ks < kMaxSamples || j0 + 2 >= a.Nb) {
+        const int nv = valid_in_block(j0 + hl);
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (i >= nv) acc[i] = -INFINITY;
+      }
+      float mraw = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, acc[i]);
+      const float mij = mraw * a.scale;                  // block-row maximum, Alg. 1 step 12
+      rt[(j0 + hl) * 32 + n] = mij;
+      // Alg. 1 steps 12-15: tile-local exponentials exp(scale * (s - max)) as one fused
+      // multiply-add and one exp2 each, then fold into the running pair
+      const float c2 = a.scale * 1.44269504088896340736f;
+      const float bias = (mraw == -INFINITY) ? 0.f : -mraw * c2;
+      float lij = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) lij += fast_exp2(fmaf(acc[i], c2, bias));
+      const float mnew = fmaxf(Mt, mij);
+      const float mnew_s = (mnew == -INFINITY) ? 0.f : mnew;
+      lt = (double)__expf(Mt - mnew_s) * lt + (double)__expf(mij - mnew_s) * (double)lij;
+      Mt = mnew;
     }
-    Rt[(j0 + hl) * 32 + n] = mij;
-    const float mnew = fmaxf(Mt, mij);
-    const float mnew_s = (mnew == -INFINITY) ? 0.f : mnew;
-    float lij = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) lij += __expf(sv[i] - mnew_s);
-    lt = (double)__expf(Mt - mnew_s) * lt + (double)lij;
-    Mt = mnew;
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) kcur[s] = knext[s];
   }
   // merge the two parities of each query
   {
@@ -124,24 +186,42 @@ __global__ __launch_bounds__(64) void probe_kernel(ProbeArgs a) {
     const float Ms = (Mall == -INFINITY) ? 0.f : Mall;
     const double lall = (double)__expf(Mt - Ms) * lt + (double)__expf(Mo - Ms) * lo;
     if (hl == 0) {
-      sM[n] = Mall;
-      sL[n] = lall;
+      sM[wave][n] = Mall;
+      sL[wave][n] = lall;
     }
   }
-  __syncthreads();
+  __syncthreads();   // also makes the wavefronts' Rt stores visible to the whole workgroup
 
+  // second sweep: wavefront w finishes query block i_base + w
+  {
+    const int i = i_base + wave;
+    if (i >= a.Nb) return;
+    const int pr_ = wave >> 1, qb = wave & 1;           // its pair and position in the pair
+    const float *rtq = a.rt + ((int64_t)work * 4 + pr_) * nb_pad * 32 + qb * 16;
+    // merge the two wavefronts of the pair
+    float Mrow[16];
+    double Lrow[16];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int i = i0 + qb;
-    if (i >= a.Nb) break;
+    for (int u = 0; u < 16; ++u) {
+      const float m0 = sM[pr_][qb * 16 + u], m1 = sM[pr_ + 4][qb * 16 + u];
+      const float mm = fmaxf(m0, m1);
+      const float ms = (mm == -INFINITY) ? 0.f : mm;
+      Mrow[u] = mm;
+      Lrow[u] = (double)__expf(m0 - ms) * sL[pr_][qb * 16 + u] +
+                (double)__expf(m1 - ms) * sL[pr_ + 4][qb * 16 + u];
+    }
     const int rows_ok = valid_in_block(i);
     float *out = a.p_imp + ((int64_t)slab * a.Nb + i) * a.Nb;
     for (int j = lane; j < a.Nb; j += 64) {
+      const f32x4 *src = reinterpret_cast<const f32x4 *>(rtq + j * 32);
+      const f32x4 r0 = src[0], r1 = src[1], r2 = src[2], r3 = src[3];
+      const float rv[16] = {r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3],
+                            r2[0], r2[1], r2[2], r2[3], r3[0], r3[1], r3[2], r3[3]};
       float best = 0.f;
-      for (int u = 0; u < rows_ok; ++u) {
-        const float rt = Rt[j * 32 + qb * 16 + u];
-        if (rt != -INFINITY) {
-          float pr = (float)((double)__expf(rt - sM[qb * 16 + u]) / sL[qb * 16 + u]);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        if (u < rows_ok && rv[u] != -INFINITY) {
+          float pr = (float)((double)__expf(rv[u] - Mrow[u]) / Lrow[u]);
           best = fmaxf(best, pr);
         }
       }
@@ -150,95 +230,138 @@ __global__ __launch_bounds__(64) void probe_kernel(ProbeArgs a) {
   }
 }
 
+size_t probe_workspace_bytes(const Problem &pb) {
+  const size_t n_groups = (pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
+  const size_t nb_pad = (pb.Nb + kProbeKBlocks - 1) / kProbeKBlocks * kProbeKBlocks;
+  return ((size_t)pb.n_slabs * n_groups * 4 * nb_pad * 32 * sizeof(float) + 255) & ~(size_t)255;
+}
+
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
-                        hipStream_t st) {
+                        void *rt_workspace, hipStream_t st) {
   ProbeArgs a;
-  a.q = q; a.k = k; a.p_imp = p_imp; a.tq = pb.q; a.tk = pb.k;
+  a.q = q; a.k = k; a.p_imp = p_imp; a.rt = reinterpret_cast<float *>(rt_workspace);
+  a.tq = pb.q; a.tk = pb.k;
   a.H = pb.H; a.L = pb.L; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs; a.block = pb.block; a.ks = pb.ks;
   a.scale = pb.scale;
   for (int u = 0; u < kMaxSamples; ++u) a.offs[u] = pb.offs[u];
   a.n_valid_last = 0;
   for (int u = 0; u < pb.ks; ++u)
     if ((int64_t)(pb.Nb - 1) * pb.block + pb.offs[u] < pb.L) ++a.n_valid_last;
-  const int n_pairs = (pb.Nb + 1) / 2;
-  const int grid = xcd_grid(pb.n_slabs * n_pairs);
-  const size_t lds = (size_t)n_pairs * 2 * 32 * sizeof(float);
+  const int n_groups = (pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
+  const int grid = xcd_grid(pb.n_slabs * n_groups);
+  const int lds = 2 * kProbeKBlocks * 16 * pb.d * 2;   // two chunks of sampled key rows
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       2 * kProbeKBlocks * 16 * 128 * 2);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   if (pb.d == 128)
-    hipLaunchKernelGGL(probe_kernel<128>, dim3(grid), dim3(64), lds, st, a);
+    hipLaunchKernelGGL(probe_kernel<128>, dim3(grid), dim3(512), lds, st, a);
   else
-    hipLaunchKernelGGL(probe_kernel<64>, dim3(grid), dim3(64), lds, st, a);
+    hipLaunchKernelGGL(probe_kernel<64>, dim3(grid), dim3(512), lds, st, a);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
 // Threshold rule (Alg. 3 steps 6-11), one workgroup per row of the importance map.
-// rank_j = number of blocks that come before j in (score descending, index ascending) order;
-// scores are scattered to rank order, their fp64 running sums c_r are formed in that order
-// (one lane, so the additions happen in exactly the sequence the algorithm states), then
-// m* = #{r : c_r < tau * T}, m = clamp(m*, m_min, m_max), keep rank < m.
+// The row is sorted by (score descending, block index ascending) with a bitonic network on
+// 64-bit keys (inverted order-preserving image of the fp32 score in the high word, the block
+// index in the low word).  One lane then forms the fp64 running sums c_r in rank order -- the
+// additions happen in exactly the sequence the algorithm states, so the decision is
+// bit-identical to a sequential implementation -- then m* = #{r : c_r < tau * T},
+// m = clamp(m*, m_min, m_max), keep rank < m.  A NaN score counts as 0.
 // ---------------------------------------------------------------------------------------
 struct RuleArgs {
   const float *scores;
   uint8_t *mask;
-  int Nb, m_min, m_max, n_prefix_blocks;
+  int Nb, n_rows, m_min, m_max, n_prefix_blocks;
   float tau;
 };
 
+__device__ __forceinline__ uint32_t desc_key(float v) {
+  v = (v == v) ? v + 0.0f : 0.0f;                 // NaN -> 0, -0 -> +0
+  uint32_t u = __float_as_uint(v);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending order-preserving image
+  return ~u;                                       // larger score -> smaller key
+}
+__device__ __forceinline__ float key_score(uint32_t k) {
+  uint32_t u = ~k;
+  u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+  return __uint_as_float(u);
+}
+
+// One wavefront per row (4 rows per workgroup): every step below is wave-synchronous, so the
+// sorting network needs no workgroup barriers, and the sequential running sums of different
+// rows run on different SIMDs.
+template <int NPAD>
 __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
-  __shared__ float p[kMaxNb];
-  __shared__ float sorted[kMaxNb];
-  __shared__ double cum[kMaxNb + 1];
-  __shared__ int mstar;
-  const int row = blockIdx.x;          // slab * Nb + i
+  __shared__ unsigned long long keys_all[4][NPAD];
+  __shared__ double cum_all[4][NPAD];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;          // slab * Nb + i
+  if (row >= a.n_rows) return;                     // whole wavefront; no workgroup barriers below
+  unsigned long long *keys = keys_all[wave];
+  double *cum = cum_all[wave];
   const int i = row % a.Nb;
-  const int tid = threadIdx.x;
   const float *src = a.scores + (int64_t)row * a.Nb;
-  for (int j = tid; j < a.Nb; j += 256) {
-    float v = src[j];
-    p[j] = (v == v) ? v : 0.f;
-  }
-  if (tid == 0) mstar = 0;
-  __syncthreads();
-  int rank[kMaxNb / 256];
+  for (int j = lane; j < NPAD; j += 64)
+    keys[j] = j < a.Nb ? (((unsigned long long)desc_key(src[j]) << 32) | (unsigned)j)
+                       : ~0ull;        // padding sorts last
+  __builtin_amdgcn_wave_barrier();
+  for (int k = 2; k <= NPAD; k <<= 1)
+    for (int jj = k >> 1; jj > 0; jj >>= 1) {
 #pragma unroll
-  for (int t = 0; t < kMaxNb / 256; ++t) {
-    const int j = tid + t * 256;
-    rank[t] = 0;
-    if (j < a.Nb) {
-      const float pj = p[j];
-      int r = 0;
-      for (int l = 0; l < a.Nb; ++l) {
-        const float pl = p[l];
-        r += (pl > pj) || (pl == pj && l < j);
+      for (int t0 = 0; t0 < NPAD / 2; t0 += 64) {
+        const int t = t0 + lane;
+        const int lo = ((t & ~(jj - 1)) << 1) | (t & (jj - 1));
+        const int hi = lo + jj;
+        const unsigned long long x = keys[lo], y = keys[hi];
+        const bool up = (lo & k) == 0;
+        if ((x > y) == up) {
+          keys[lo] = y;
+          keys[hi] = x;
+        }
       }
-      rank[t] = r;
-      sorted[r] = pj;
+      __builtin_amdgcn_wave_barrier();
     }
-  }
-  __syncthreads();
-  if (tid == 0) {
+  // scores in rank order as fp64 (in parallel), zero-padded
+  for (int r = lane; r < NPAD; r += 64)
+    cum[r] = r < a.Nb ? (double)key_score((uint32_t)(keys[r] >> 32)) : 0.0;
+  __builtin_amdgcn_wave_barrier();
+  // Running sums in place: cum[r] becomes c_{r+1} = sum of the r+1 best scores.  Sequential on
+  // purpose (see above): one lane, eight values fetched at a time so that only the additions
+  // sit on the dependent chain.
+  if (lane == 0) {
     double c = 0.0;
-    cum[0] = 0.0;
-    for (int r = 0; r < a.Nb; ++r) {
-      c = c + (double)sorted[r];
-      cum[r + 1] = c;
+    for (int r0 = 0; r0 < a.Nb; r0 += 8) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = cum[r0 + u];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        c = c + v[u];
+        v[u] = c;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cum[r0 + u] = v[u];
     }
   }
-  __syncthreads();
-  const double thr = (double)a.tau * cum[a.Nb];
+  __builtin_amdgcn_wave_barrier();
+  const double thr = (double)a.tau * cum[a.Nb - 1];   // tau * T
   int inside = 0;
-  for (int r = tid; r < a.Nb; r += 256) inside += (cum[r] < thr);
-  if (inside) atomicAdd(&mstar, inside);
-  __syncthreads();
-  int m = mstar;
+  for (int r = lane; r < a.Nb; r += 64) inside += ((r == 0 ? 0.0 : cum[r - 1]) < thr);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) inside += __shfl_xor(inside, off, 64);
+  int m = inside;
   m = m < a.m_min ? a.m_min : m;
   m = m > a.m_max ? a.m_max : m;
   uint8_t *dst = a.mask + (int64_t)row * a.Nb;
-#pragma unroll
-  for (int t = 0; t < kMaxNb / 256; ++t) {
-    const int j = tid + t * 256;
-    if (j < a.Nb)
-      dst[j] = (rank[t] < m) || (i < a.n_prefix_blocks) || (j < a.n_prefix_blocks);
+  for (int r = lane; r < a.Nb; r += 64) {
+    const int j = (int)(keys[r] & 0xffffffffu);
+    dst[j] = (r < m) || (i < a.n_prefix_blocks) || (j < a.n_prefix_blocks);
   }
 }
 
@@ -246,81 +369,100 @@ hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hi
   RuleArgs a;
   a.scores = scores; a.mask = mask; a.Nb = pb.Nb; a.m_min = pb.m_min; a.m_max = pb.m_max;
   a.n_prefix_blocks = pb.n_prefix_blocks; a.tau = pb.tau;
-  hipLaunchKernelGGL(rule_kernel, dim3(pb.n_slabs * pb.Nb), dim3(256), 0, st, a);
+  a.n_rows = pb.n_slabs * pb.Nb;
+  const dim3 grid((a.n_rows + 3) / 4), block(256);
+  // network size: power of two >= Nb (and >= 128 so that every lane owns a pair)
+  if (pb.Nb <= 128) hipLaunchKernelGGL(rule_kernel<128>, grid, block, 0, st, a);
+  else if (pb.Nb <= 256) hipLaunchKernelGGL(rule_kernel<256>, grid, block, 0, st, a);
+  else if (pb.Nb <= 512) hipLaunchKernelGGL(rule_kernel<512>, grid, block, 0, st, a);
+  else hipLaunchKernelGGL(rule_kernel<1024>, grid, block, 0, st, a);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
-// Index lists.  blockIdx.x = slab, blockIdx.y = 0: by rows (CSR), 1: by columns (CSC).
-// Both walk the mask row by row so that every load is coalesced: the CSR side gives a
-// wavefront one row at a time (64 columns per step, positions from a ballot), the CSC side
-// gives every thread one column.
+// Index lists of a mask, by rows (CSR) and by columns (CSC), in three small fully parallel
+// kernels: count (one workgroup per row i and column i), in-place scan of the counts, fill.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void csr_kernel(const uint8_t *mask, int Nb, int32_t *row_ptr,
-                                                  int32_t *col_idx, int32_t *col_ptr,
-                                                  int32_t *row_idx) {
-  __shared__ int cnt[kMaxNb + 1];
-  const bool by_col = blockIdx.y == 1;
-  int32_t *ptr = by_col ? col_ptr : row_ptr;
-  int32_t *idx = by_col ? row_idx : col_idx;
-  if (ptr == nullptr) return;
-  const int slab = blockIdx.x;
+// blockIdx = (i, slab).  Wavefront 0 counts row i (coalesced), wavefront 1 counts column i.
+__global__ __launch_bounds__(128) void csr_count_kernel(const uint8_t *mask, int Nb,
+                                                        int32_t *row_ptr, int32_t *col_ptr) {
+  const int i = blockIdx.x, slab = blockIdx.y;
   const uint8_t *m = mask + (int64_t)slab * Nb * Nb;
-  ptr += (int64_t)slab * (Nb + 1);
-  idx += (int64_t)slab * Nb * Nb;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int32_t *ptr = wave == 0 ? row_ptr : col_ptr;
+  if (ptr == nullptr) return;
+  int n = 0;
+  for (int x0 = 0; x0 < Nb; x0 += 64) {
+    const int x = x0 + lane;
+    const bool f = x < Nb && (wave == 0 ? m[(int64_t)i * Nb + x] : m[(int64_t)x * Nb + i]) != 0;
+    n += __popcll(__ballot(f));
+  }
+  if (lane == 0) {
+    ptr[(int64_t)slab * (Nb + 1) + i + 1] = n;
+    if (i == 0) ptr[(int64_t)slab * (Nb + 1)] = 0;
+  }
+}
 
-  if (by_col) {
-    for (int c = tid; c < Nb; c += 256) {
-      int n = 0;
-      for (int r = 0; r < Nb; ++r) n += m[(int64_t)r * Nb + c] != 0;
-      cnt[c] = n;
-    }
-  } else {
-    for (int r = wave; r < Nb; r += 4) {
-      int n = 0;
-      for (int c0 = 0; c0 < Nb; c0 += 64) {
-        const bool f = (c0 + lane < Nb) && m[(int64_t)r * Nb + c0 + lane] != 0;
-        n += __popcll(__ballot(f));
-      }
-      if (lane == 0) cnt[r] = n;
-    }
-  }
+// blockIdx = (slab, 0: rows / 1: columns).  Inclusive scan of ptr[1..Nb] in place.
+__global__ __launch_bounds__(256) void csr_scan_kernel(int Nb, int32_t *row_ptr, int32_t *col_ptr) {
+  __shared__ int part[256];
+  int32_t *ptr = blockIdx.y == 0 ? row_ptr : col_ptr;
+  if (ptr == nullptr) return;
+  ptr += (int64_t)blockIdx.x * (Nb + 1) + 1;
+  const int tid = threadIdx.x;
+  const int per = (Nb + 255) / 256;
+  const int lo = tid * per;
+  int sum = 0;
+  for (int x = lo; x < lo + per && x < Nb; ++x) sum += ptr[x];
+  part[tid] = sum;
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int r = 0; r < Nb; ++r) {
-      int c = cnt[r];
-      cnt[r] = run;
-      run += c;
-    }
-    cnt[Nb] = run;
+  for (int off = 1; off < 256; off <<= 1) {
+    int v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
   }
-  __syncthreads();
-  for (int r = tid; r <= Nb; r += 256) ptr[r] = cnt[r];
-  if (by_col) {
-    for (int c = tid; c < Nb; c += 256) {
-      int o = cnt[c];
-      for (int r = 0; r < Nb; ++r)
-        if (m[(int64_t)r * Nb + c] != 0) idx[o++] = r;
-    }
-  } else {
-    for (int r = wave; r < Nb; r += 4) {
-      int o = cnt[r];
-      for (int c0 = 0; c0 < Nb; c0 += 64) {
-        const bool f = (c0 + lane < Nb) && m[(int64_t)r * Nb + c0 + lane] != 0;
-        const unsigned long long b = __ballot(f);
-        if (f) idx[o + __popcll(b & ((1ull << lane) - 1ull))] = c0 + lane;
-        o += __popcll(b);
-      }
-    }
+  int run = part[tid] - sum;   // exclusive prefix of my segment
+  for (int x = lo; x < lo + per && x < Nb; ++x) {
+    run += ptr[x];
+    ptr[x] = run;
+  }
+}
+
+// blockIdx = (i, slab).  Wavefront 0 writes the kept columns of row i, wavefront 1 the kept
+// rows of column i, both ascending (ballot compaction, 64 entries per step).
+__global__ __launch_bounds__(128) void csr_fill_kernel(const uint8_t *mask, int Nb,
+                                                       const int32_t *row_ptr, int32_t *col_idx,
+                                                       const int32_t *col_ptr, int32_t *row_idx) {
+  const int i = blockIdx.x, slab = blockIdx.y;
+  const uint8_t *m = mask + (int64_t)slab * Nb * Nb;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int32_t *ptr = wave == 0 ? row_ptr : col_ptr;
+  int32_t *idx = wave == 0 ? col_idx : row_idx;
+  if (ptr == nullptr) return;
+  int o = ptr[(int64_t)slab * (Nb + 1) + i];
+  idx += (int64_t)slab * Nb * Nb;
+  for (int x0 = 0; x0 < Nb; x0 += 64) {
+    const int x = x0 + lane;
+    const bool f = x < Nb && (wave == 0 ? m[(int64_t)i * Nb + x] : m[(int64_t)x * Nb + i]) != 0;
+    const unsigned long long b = __ballot(f);
+    if (f) idx[o + __popcll(b & ((1ull << lane) - 1ull))] = x;
+    o += __popcll(b);
   }
 }
 
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st) {
-  hipLaunchKernelGGL(csr_kernel, dim3(pb.n_slabs, 2), dim3(256), 0, st, mask, pb.Nb, row_ptr,
-                     col_idx, col_ptr, row_idx);
+  hipLaunchKernelGGL(csr_count_kernel, dim3(pb.Nb, pb.n_slabs), dim3(128), 0, st, mask, pb.Nb,
+                     row_ptr, col_ptr);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(csr_scan_kernel, dim3(pb.n_slabs, 2), dim3(256), 0, st, pb.Nb, row_ptr,
+                     col_ptr);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(csr_fill_kernel, dim3(pb.Nb, pb.n_slabs), dim3(128), 0, st, mask, pb.Nb,
+                     row_ptr, col_idx, col_ptr, row_idx);
   return hipGetLastError();
 }
 

@@ -42,8 +42,10 @@ class _Case:
         p0 = binding.Params(**{**p.__dict__, "n_prefix_dense": 0})
         self.gp = torch.empty((w.B * w.H, p.Nb, p.Nb), dtype=torch.float32, device="cuda")
         free = binding.alloc_index_lists(p0, with_csc=False)
+        ws = binding.alloc_workspace(binding.asa_mask_workspace_bytes(p0))
         binding.asa_build_mask(p0, q, k, free["mask"], free["row_ptr"], free["col_idx"], None, None,
-                               self.gp)
+                               self.gp, ws)
+        del ws
         self.gmask_free = free["mask"].cpu().numpy()
         self.gp = self.gp.cpu().numpy()
         # the forward / backward run on the ORACLE's mask (uploaded), in the bench's launch shape

@@ -81,8 +81,9 @@ def test_index_lists_match_the_mask(Nb, dens):
 def _build(p, qb, kb, want_csc=True):
     bufs = binding.alloc_index_lists(p, with_csc=want_csc)
     pimp = torch.empty((p.B * p.H, p.Nb, p.Nb), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(binding.asa_mask_workspace_bytes(p))
     binding.asa_build_mask(p, util.dev_bf16(qb), util.dev_bf16(kb), bufs["mask"], bufs["row_ptr"],
-                           bufs["col_idx"], bufs.get("col_ptr"), bufs.get("row_idx"), pimp)
+                           bufs["col_idx"], bufs.get("col_ptr"), bufs.get("row_idx"), pimp, ws)
     torch.cuda.synchronize()
     return bufs, pimp.cpu().numpy()
 
