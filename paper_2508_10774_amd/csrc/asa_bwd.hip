@@ -15,17 +15,12 @@
 //               wave's 32 keys resident in registers; bf16(P) and bf16(dS) are the B operands of
 //               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T tiles from per-block transposed copies).
 #include "asa_common.hpp"
+#include "asa_tiles.hpp"
 
 namespace asa {
 
-__device__ __forceinline__ int kappa_b(int r) {
-  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
-  return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + j;
-}
-__device__ __forceinline__ int rho_b(int r) {
-  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
-  return 16 * h + 4 * g + j;
-}
+__device__ __forceinline__ int kappa_b(int r) { return kappa(r); }
+__device__ __forceinline__ int rho_b(int r) { return rho(r); }
 
 constexpr float kLog2e = 1.44269504088896340736f;
 
@@ -78,69 +73,50 @@ struct BwdArgs {
 
 template <int BLK, int D>
 struct BwdCfg {
-  static constexpr int kThreads = BLK * 2;
-  static constexpr int kRowStride = D + 8;   // row-major tile [BLK][D]
-  static constexpr int kColStride = BLK + 8;  // transposed tile [D][BLK]
-  static constexpr int kRowTile = BLK * kRowStride;
-  static constexpr int kColTile = D * kColStride;
+  static constexpr int kWaves = BLK / 32;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kST = 64;                 // rows (keys or queries) per step
+  static constexpr int kSub = BLK / kST;         // steps per block
+  static constexpr int kRowTile = kST * D;       // [64][D]  elements, swizzled, unpadded
+  static constexpr int kColTile = D * kST;       // [D][64]
   static constexpr int kDqLds = (2 * kRowTile + kColTile) * 2;
-  static constexpr int kDkvLds = (2 * kRowTile + 2 * kColTile) * 2 + 2 * BLK * 4;
+  static constexpr int kDvLds = (kRowTile + kColTile) * 2 + 2 * kST * 4;
+  static constexpr int kDkLds = (2 * kRowTile + kColTile) * 2 + 2 * kST * 4;
 };
 
-// copy a [BLK][D] row-major tile (rows clamped to L-1) into LDS
-template <int BLK, int D, int THREADS>
-__device__ __forceinline__ void load_row_tile(bf16 *dst, const bf16 *src, int64_t sL, int row0,
-                                              int L, int tid) {
-  constexpr int CH = D / 8;
-#pragma unroll
-  for (int i = 0; i < BLK * CH / THREADS; ++i) {
-    int c = tid + i * THREADS;
-    int r = c / CH, cc = c % CH;
-    int row = row0 + r;
-    row = row < L ? row : L - 1;
-    uint4 val = *reinterpret_cast<const uint4 *>(src + (int64_t)row * sL + cc * 8);
-    *reinterpret_cast<uint4 *>(dst + r * (D + 8) + cc * 8) = val;
-  }
-}
-// copy transposed tile `blk` ([D][BLK], contiguous) of a [Nb][d][block] array into LDS
-template <int BLK, int D, int THREADS>
-__device__ __forceinline__ void load_col_tile(bf16 *dst, const bf16 *src, int blk, int tid) {
-  constexpr int CV = BLK / 8;
-  const bf16 *tile = src + (int64_t)blk * D * BLK;
-#pragma unroll
-  for (int i = 0; i < D * CV / THREADS; ++i) {
-    int c = tid + i * THREADS;
-    int r = c / CV, cc = c % CV;
-    uint4 val = *reinterpret_cast<const uint4 *>(tile + c * 8);
-    *reinterpret_cast<uint4 *>(dst + r * (BLK + 8) + cc * 8) = val;
-  }
-}
-
 // ---------------------------------------------------------------------------------------
-// dQ: one workgroup per query block, one wavefront per 32 query rows.
+// dQ: one workgroup per query block, one wavefront per 32 query rows.  Per step of 64 keys the
+// workgroup copies K rows, V rows and the matching K^T slice straight into LDS; two
+// workgroups share a CU, so one computes while the other's copies are in flight.
 // ---------------------------------------------------------------------------------------
 template <int BLK, int D>
-__global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
+__global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   using C = BwdCfg<BLK, D>;
-  extern __shared__ __align__(16) unsigned char smem[];
+  extern __shared__ __align__(1024) unsigned char smem[];
   bf16 *Ks = reinterpret_cast<bf16 *>(smem);
   bf16 *Vs = Ks + C::kRowTile;
   bf16 *Kt = Vs + C::kRowTile;
+  __shared__ int cols[kMaxNb];
 
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
   const int slab = work / a.Nb;
   const int qb = work - slab * a.Nb;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hl = lane >> 5, n = lane & 31;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, hl = lane >> 5, n = lane & 31;
 
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vs = slab_ptr(a.v, a.tv, slab, a.H);
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
   const bf16 *kts = a.kt + (int64_t)slab * D * a.Lpad;
-  const int32_t *cols = a.col_idx + (int64_t)slab * a.Nb * a.Nb;
   const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int t_end = a.row_ptr[slab * (a.Nb + 1) + qb + 1];
+  const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  {
+    const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
+    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = g[t];
+  }
 
   const int qrow = qb * BLK + wave * 32 + n;
   const bool qvalid = qrow < a.L;
@@ -161,28 +137,41 @@ __global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[dm][i] = 0.f;
 
-  const int row_off = kappa_b(n) * C::kRowStride + 8 * hl;
-  const int col_off = rho_b(n) * C::kColStride + 8 * hl;
-  const float c = a.scale_log2e;
+  RowTileCopy<C::kST, D, C::kWaves> copy_k, copy_v;
+  ColTileCopy<BLK, D, C::kWaves> copy_kt;
+  copy_k.init(wave, lane, a.tk.sL);
+  copy_v.init(wave, lane, a.tv.sL);
+  copy_kt.init(wave, lane);
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const int j = cols[t];
+  // A fragments: rows kappa(n) of a 32-key group (K, V), rows rho(n) of a 32-channel group (K^T)
+  const int kr = kappa_b(n), cr = rho_b(n);
+  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  const float c = a.scale_log2e;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  const int n_steps = n_tiles * C::kSub;
+  for (int step = 0; step < n_steps; ++step) {
+    __syncthreads();   // the previous step's fragments are consumed (and cols[] is written)
+    const int j = cols[step / C::kSub];
+    const int sub = step % C::kSub;
+    const int key0 = j * BLK + sub * C::kST;
+    copy_k.issue(Ks, ks, key0, a.L);
+    copy_v.issue(Vs, vs, key0, a.L);
+    copy_kt.issue(Kt, kts + (int64_t)j * D * BLK, sub * C::kST);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
-    load_row_tile<BLK, D, C::kThreads>(Ks, ks, a.tk.sL, j * BLK, a.L, tid);
-    load_row_tile<BLK, D, C::kThreads>(Vs, vs, a.tv.sL, j * BLK, a.L, tid);
-    load_col_tile<BLK, D, C::kThreads>(Kt, kts, j, tid);
-    __syncthreads();
-    const bool tail = j * BLK + BLK > a.L;
+    const bool tail = key0 + C::kST > a.L;
 #pragma unroll
-    for (int mt = 0; mt < BLK / 32; ++mt) {
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+    for (int mt = 0; mt < C::kST / 32; ++mt) {
+      const bf16 *krow = Ks + (mt * 32 + kr) * D;
+      const bf16 *vrow = Vs + (mt * 32 + kr) * D;
+      f32x16 sacc = zero16, pacc = zero16;
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(Ks + mt * 32 * C::kRowStride + row_off + 16 * s);
+        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(krow + ((16 * s) ^ kx));
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc, 0, 0, 0);
-        bf16x8 va = *reinterpret_cast<const bf16x8 *>(Vs + mt * 32 * C::kRowStride + row_off + 16 * s);
+        bf16x8 va = *reinterpret_cast<const bf16x8 *>(vrow + ((16 * s) ^ kx));
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[s], pacc, 0, 0, 0);
       }
       uint32_t dsb[8];
@@ -191,7 +180,7 @@ __global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
         float p0 = fast_exp2(fmaf(sacc[i], c, -lse2));
         float p1 = fast_exp2(fmaf(sacc[i + 1], c, -lse2));
         if (tail) {
-          int key = j * BLK + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
+          int key = key0 + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
           if (key >= a.L) p0 = 0.f;
           if (key + 1 >= a.L) p1 = 0.f;
         }
@@ -203,8 +192,8 @@ __global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
         bf16x8 dsf = *reinterpret_cast<bf16x8 *>(&raw);
 #pragma unroll
         for (int dm = 0; dm < D / 32; ++dm) {
-          bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Kt + dm * 32 * C::kColStride + col_off +
-                                                        16 * (2 * mt + tt));
+          bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Kt + (dm * 32 + cr) * C::kST +
+                                                        ((16 * (2 * mt + tt)) ^ cx));
           acc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, dsf, acc[dm], 0, 0, 0);
         }
       }
@@ -227,24 +216,34 @@ __global__ __launch_bounds__(BLK * 2, 1) void dq_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// dK, dV: one workgroup per key block, one wavefront per 32 keys.
+// dK, dV: one workgroup per key block, one wavefront per 32 keys (its K and V rows stay in
+// registers as B operands).  Per step of 64 queries: Q rows, dO rows, Q^T and dO^T slices,
+// LSE and Delta go to LDS.  The kernel is instantiated twice, WHAT = 0 for dV (needs S and P
+// only) and WHAT = 1 for dK (needs S, dP and dS): holding both 32 x d fp32 accumulators plus
+// the K and V operands in one wavefront exceeds the register budget of two wavefronts per
+// SIMD, and recomputing S (one extra tile product) is cheaper than running at half occupancy.
 // ---------------------------------------------------------------------------------------
-template <int BLK, int D>
-__global__ __launch_bounds__(BLK * 2, 1) void dkv_kernel(BwdArgs a) {
+template <int BLK, int D, int WHAT>
+__global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
+  constexpr bool DO_DV = WHAT == 0, DO_DK = WHAT == 1;
   using C = BwdCfg<BLK, D>;
-  extern __shared__ __align__(16) unsigned char smem[];
+  extern __shared__ __align__(1024) unsigned char smem[];
+  // dV uses {Q rows, dO^T slice}; dK uses {Q rows, dO rows, Q^T slice}
   bf16 *Qs = reinterpret_cast<bf16 *>(smem);
-  bf16 *Gs = Qs + C::kRowTile;
-  bf16 *Qt = Gs + C::kRowTile;
-  bf16 *Gt = Qt + C::kColTile;
-  float *sLse = reinterpret_cast<float *>(Gt + C::kColTile);
-  float *sDelta = sLse + BLK;
+  bf16 *Gs = Qs + C::kRowTile;                       // dK only
+  bf16 *Qt = Gs + C::kRowTile;                       // dK only
+  bf16 *Gt = Qs + C::kRowTile;                       // dV only (same place as Gs)
+  float *sLse = reinterpret_cast<float *>(DO_DV ? Gt + C::kColTile : Qt + C::kColTile);
+  float *sDelta = sLse + C::kST;
+  __shared__ int rows[kMaxNb];
 
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
   const int slab = work / a.Nb;
   const int kb = work - slab * a.Nb;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hl = lane >> 5, n = lane & 31;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, hl = lane >> 5, n = lane & 31;
 
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
@@ -252,9 +251,12 @@ __global__ __launch_bounds__(BLK * 2, 1) void dkv_kernel(BwdArgs a) {
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
   const bf16 *qts = a.qt + (int64_t)slab * D * a.Lpad;
   const bf16 *gts = a.dot + (int64_t)slab * D * a.Lpad;
-  const int32_t *rows = a.row_idx + (int64_t)slab * a.Nb * a.Nb;
   const int t_begin = a.col_ptr[slab * (a.Nb + 1) + kb];
-  const int t_end = a.col_ptr[slab * (a.Nb + 1) + kb + 1];
+  const int n_tiles = a.col_ptr[slab * (a.Nb + 1) + kb + 1] - t_begin;
+  {
+    const int32_t *g = a.row_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
+    for (int t = tid; t < n_tiles; t += C::kThreads) rows[t] = g[t];
+  }
 
   const int krow = kb * BLK + wave * 32 + n;
   const bool kvalid = krow < a.L;
@@ -263,99 +265,116 @@ __global__ __launch_bounds__(BLK * 2, 1) void dkv_kernel(BwdArgs a) {
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     kreg[s] = *reinterpret_cast<const bf16x8 *>(ks + (int64_t)krow_c * a.tk.sL + 16 * s + 8 * hl);
-    vreg[s] = *reinterpret_cast<const bf16x8 *>(vs + (int64_t)krow_c * a.tv.sL + 16 * s + 8 * hl);
+    if (DO_DK)
+      vreg[s] = *reinterpret_cast<const bf16x8 *>(vs + (int64_t)krow_c * a.tv.sL + 16 * s + 8 * hl);
   }
-  f32x16 dkacc[D / 32], dvacc[D / 32];
+  f32x16 gacc[D / 32];   // dV^T (WHAT = 0) or dK^T (WHAT = 1) of my 32 keys
 #pragma unroll
   for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { dkacc[dm][i] = 0.f; dvacc[dm][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) gacc[dm][i] = 0.f;
 
-  const int row_off = kappa_b(n) * C::kRowStride + 8 * hl;
-  const int col_off = rho_b(n) * C::kColStride + 8 * hl;
+  RowTileCopy<C::kST, D, C::kWaves> copy_q, copy_g;
+  ColTileCopy<BLK, D, C::kWaves> copy_t;
+  copy_q.init(wave, lane, a.tq.sL);
+  copy_g.init(wave, lane, a.to.sL);
+  copy_t.init(wave, lane);
+
+  const int kr = kappa_b(n), cr = rho_b(n);
+  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
   const float c = a.scale_log2e;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const int i_blk = rows[t];
+  const int n_steps = n_tiles * C::kSub;
+  for (int step = 0; step < n_steps; ++step) {
     __syncthreads();
-    load_row_tile<BLK, D, C::kThreads>(Qs, qs, a.tq.sL, i_blk * BLK, a.L, tid);
-    load_row_tile<BLK, D, C::kThreads>(Gs, gs, a.to.sL, i_blk * BLK, a.L, tid);
-    load_col_tile<BLK, D, C::kThreads>(Qt, qts, i_blk, tid);
-    load_col_tile<BLK, D, C::kThreads>(Gt, gts, i_blk, tid);
-    if (tid < BLK) {
-      int r = i_blk * BLK + tid;
-      bool ok = r < a.L;
-      sLse[tid] = ok ? a.lse[(int64_t)slab * a.L + r] * kLog2e : INFINITY;
-      sDelta[tid] = ok ? a.delta[(int64_t)slab * a.L + r] : 0.f;
+    const int i_blk = rows[step / C::kSub];
+    const int sub = step % C::kSub;
+    const int q0 = i_blk * BLK + sub * C::kST;
+    copy_q.issue(Qs, qs, q0, a.L);
+    if (DO_DK) {
+      copy_g.issue(Gs, gs, q0, a.L);
+      copy_t.issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST);
+    } else {
+      copy_t.issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST);
     }
+    if (tid < C::kST) {
+      const int r = q0 + tid;
+      const bool ok = r < a.L;
+      sLse[tid] = ok ? a.lse[(int64_t)slab * a.L + r] * kLog2e : INFINITY;
+      if (DO_DK) sDelta[tid] = ok ? a.delta[(int64_t)slab * a.L + r] : 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
 #pragma unroll
-    for (int mt = 0; mt < BLK / 32; ++mt) {
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+    for (int mt = 0; mt < C::kST / 32; ++mt) {
+      const bf16 *qrow = Qs + (mt * 32 + kr) * D;
+      const bf16 *grow = Gs + (mt * 32 + kr) * D;
+      f32x16 sacc = zero16, pacc = zero16;
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        bf16x8 qa = *reinterpret_cast<const bf16x8 *>(Qs + mt * 32 * C::kRowStride + row_off + 16 * s);
+        bf16x8 qa = *reinterpret_cast<const bf16x8 *>(qrow + ((16 * s) ^ kx));
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
-        bf16x8 ga = *reinterpret_cast<const bf16x8 *>(Gs + mt * 32 * C::kRowStride + row_off + 16 * s);
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
+        if (DO_DK) {
+          bf16x8 ga = *reinterpret_cast<const bf16x8 *>(grow + ((16 * s) ^ kx));
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
+        }
       }
       // accumulator register i of lane half hl is query 32mt + 16(i/8) + 8hl + (i%8)
       uint32_t pb[8], dsb[8];
 #pragma unroll
       for (int t8 = 0; t8 < 2; ++t8) {
-        const int q0 = mt * 32 + 16 * t8 + 8 * hl;
-        f32x4 l0 = *reinterpret_cast<const f32x4 *>(sLse + q0);
-        f32x4 l1 = *reinterpret_cast<const f32x4 *>(sLse + q0 + 4);
-        f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + q0);
-        f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + q0 + 4);
+        const int qq = mt * 32 + 16 * t8 + 8 * hl;
+        f32x4 l0 = *reinterpret_cast<const f32x4 *>(sLse + qq);
+        f32x4 l1 = *reinterpret_cast<const f32x4 *>(sLse + qq + 4);
         float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
-        float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+        float dv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (DO_DK) {
+          f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + qq);
+          f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + qq + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { dv[e] = d0[e]; dv[4 + e] = d1[e]; }
+        }
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
           const int i = 8 * t8 + e;
           float p0 = kvalid ? fast_exp2(fmaf(sacc[i], c, -lv[e])) : 0.f;
           float p1 = kvalid ? fast_exp2(fmaf(sacc[i + 1], c, -lv[e + 1])) : 0.f;
-          pb[i >> 1] = pack_bf16x2(p0, p1);
-          dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - dv[e]), p1 * (pacc[i + 1] - dv[e + 1]));
+          if (DO_DV) pb[i >> 1] = pack_bf16x2(p0, p1);
+          if (DO_DK)
+            dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - dv[e]), p1 * (pacc[i + 1] - dv[e + 1]));
         }
       }
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        uint4 praw = make_uint4(pb[4 * tt], pb[4 * tt + 1], pb[4 * tt + 2], pb[4 * tt + 3]);
-        uint4 draw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
-        bf16x8 pf = *reinterpret_cast<bf16x8 *>(&praw);
-        bf16x8 df = *reinterpret_cast<bf16x8 *>(&draw);
+        const uint32_t *w = DO_DV ? pb : dsb;
+        uint4 raw = make_uint4(w[4 * tt], w[4 * tt + 1], w[4 * tt + 2], w[4 * tt + 3]);
+        bf16x8 bf = *reinterpret_cast<bf16x8 *>(&raw);
+        const bf16 *tile = DO_DV ? Gt : Qt;   // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
         for (int dm = 0; dm < D / 32; ++dm) {
-          const int off = dm * 32 * C::kColStride + col_off + 16 * (2 * mt + tt);
-          bf16x8 ga = *reinterpret_cast<const bf16x8 *>(Gt + off);
-          dvacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pf, dvacc[dm], 0, 0, 0);
-          bf16x8 qa = *reinterpret_cast<const bf16x8 *>(Qt + off);
-          dkacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, df, dkacc[dm], 0, 0, 0);
+          const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
+          bf16x8 ta = *reinterpret_cast<const bf16x8 *>(tile + off);
+          gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bf, gacc[dm], 0, 0, 0);
         }
       }
     }
   }
 
   if (kvalid) {
-    bf16 *dk_row = slab_ptr(a.dk, a.tk, slab, a.H) + (int64_t)krow * a.tk.sL;
-    bf16 *dv_row = slab_ptr(a.dv, a.tv, slab, a.H) + (int64_t)krow * a.tv.sL;
+    bf16 *out_row = DO_DV ? slab_ptr(a.dv, a.tv, slab, a.H) + (int64_t)krow * a.tv.sL
+                          : slab_ptr(a.dk, a.tk, slab, a.H) + (int64_t)krow * a.tk.sL;
+    const float mul = DO_DV ? 1.f : a.scale;
 #pragma unroll
     for (int dm = 0; dm < D / 32; ++dm) {
-      uint32_t wk[8], wv[8];
+      uint32_t w[8];
 #pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        wk[i >> 1] = pack_bf16x2(dkacc[dm][i] * a.scale, dkacc[dm][i + 1] * a.scale);
-        wv[i >> 1] = pack_bf16x2(dvacc[dm][i], dvacc[dm][i + 1]);
-      }
-      uint4 *pk = reinterpret_cast<uint4 *>(dk_row + dm * 32 + 16 * hl);
-      pk[0] = make_uint4(wk[0], wk[1], wk[2], wk[3]);
-      pk[1] = make_uint4(wk[4], wk[5], wk[6], wk[7]);
-      uint4 *pv = reinterpret_cast<uint4 *>(dv_row + dm * 32 + 16 * hl);
-      pv[0] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-      pv[1] = make_uint4(wv[4], wv[5], wv[6], wv[7]);
+      for (int i = 0; i < 16; i += 2)
+        w[i >> 1] = pack_bf16x2(gacc[dm][i] * mul, gacc[dm][i + 1] * mul);
+      uint4 *po = reinterpret_cast<uint4 *>(out_row + dm * 32 + 16 * hl);
+      po[0] = make_uint4(w[0], w[1], w[2], w[3]);
+      po[1] = make_uint4(w[4], w[5], w[6], w[7]);
     }
   }
 }
@@ -379,15 +398,22 @@ static hipError_t launch_bwd_t(const BwdArgs &a, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkvLds);
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 0>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDvLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
   timing_begin(st);
-  hipLaunchKernelGGL((dkv_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDkvLds, st, a);
+  hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(grid), dim3(C::kThreads), C::kDvLds, st, a);
   hipError_t e = hipGetLastError();
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(grid), dim3(C::kThreads), C::kDkLds, st, a);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess) {
     hipLaunchKernelGGL((dq_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
     e = hipGetLastError();

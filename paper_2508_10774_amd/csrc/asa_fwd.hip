@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "asa_common.hpp"
+#include "asa_tiles.hpp"
 
 namespace asa {
 
@@ -95,48 +96,6 @@ struct FwdCfg {
   static constexpr int kVInstr = kVElems * 2 / 1024 / kWaves;
   static constexpr int kKChunkBits = (D == 128) ? 4 : 3;   // log2(16-byte chunks per K row)
 };
-
-// Row r of an MFMA A operand / accumulator splits as r = 8g + 4h + j (g<4, h<2, j<4); lane
-// half h holds accumulator register 4g + j.
-//
-// kappa: which key of a 32-key group is loaded as A row r of S^T = K Q^T.  Chosen so that
-// lane half h, registers 8t..8t+7 hold keys 16t + 8h + 0..7: exactly the 8 consecutive k
-// slots that the B operand of the following 16-deep P^T step wants from that lane.
-__device__ __forceinline__ int kappa(int r) {
-  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
-  return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + j;
-}
-// rho: which channel of a 32-channel group is loaded as A row r of O^T = V^T P^T, chosen so
-// that lane half h ends up with 16 consecutive channels 16h + (4g + j) of its query.
-__device__ __forceinline__ int rho(int r) {
-  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
-  return 16 * h + 4 * g + j;
-}
-
-// LDS tiles are filled by direct global->LDS loads, which write 64 lanes x 16 B contiguously:
-// rows cannot be padded, so 16-byte chunks are XOR-swizzled instead.  A K row holds D/8 chunks
-// and is read by 16 lanes with 16 different rows (kappa) and one chunk index: chunk c of row r
-// lives at position c ^ (r mod chunks).  A V^T row holds 8 chunks (128 B, half the banks) and is
-// read through rho, whose 16 rows differ in row bits 0..2 and 4: position c ^ f(r) with f built
-// from bits 1, 2, 4 separates the 8 rows of equal parity, parity itself picks the bank half.
-template <int D>
-__device__ __forceinline__ int k_swz(int row) {
-  // D = 128: a row is all 64 banks, 16 rows need 16 positions; D = 64: a row is half the banks,
-  // parity picks the half and the 8 rows of equal parity need 8 positions
-  return D == 128 ? (row & 15) : ((row >> 1) & 7);
-}
-__device__ __forceinline__ int v_swz(int row) { return ((row >> 1) & 3) | (((row >> 4) & 1) << 2); }
-
-typedef __attribute__((address_space(3))) void lds_void;
-
-// One direct global->LDS load: every lane fetches 16 bytes from its own global address and the
-// wavefront's 64 x 16 B land contiguously at the (wave-uniform) LDS address.  Counted by vmcnt.
-// (The builtin only exists in the device pass; the host pass needs no body.)
-__device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds(src, (lds_void *)lds_dst, 16, 0, 0);
-#endif
-}
 
 // The running maximum (and with it O and the row sum) is rescaled only on steps where some row
 // of the wavefront actually found a larger logit; on all other steps the factor would be 1.

@@ -1,0 +1,123 @@
+// MFMA operand orderings, LDS swizzles and direct global->LDS tile copies shared by the
+// forward and backward attention kernels (device code only).
+#pragma once
+
+#include "asa_common.hpp"
+
+namespace asa {
+
+// Row r of an MFMA A operand / accumulator splits as r = 8g + 4h + j (g<4, h<2, j<4); lane
+// half h holds accumulator register 4g + j.
+//
+// kappa: which key of a 32-key group is loaded as A row r of S^T = K Q^T.  Chosen so that
+// lane half h, registers 8t..8t+7 hold keys 16t + 8h + 0..7: exactly the 8 consecutive k
+// slots that the B operand of the following 16-deep P^T step wants from that lane.
+__device__ __forceinline__ int kappa(int r) {
+  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
+  return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + j;
+}
+// rho: which channel of a 32-channel group is loaded as A row r of O^T = V^T P^T, chosen so
+// that lane half h ends up with 16 consecutive channels 16h + (4g + j) of its query.
+__device__ __forceinline__ int rho(int r) {
+  int g = r >> 3, h = (r >> 2) & 1, j = r & 3;
+  return 16 * h + 4 * g + j;
+}
+
+// LDS tiles are filled by direct global->LDS loads, which write 64 lanes x 16 B contiguously:
+// rows cannot be padded, so 16-byte chunks are XOR-swizzled instead.  A K row holds D/8 chunks
+// and is read by 16 lanes with 16 different rows (kappa) and one chunk index: chunk c of row r
+// lives at position c ^ (r mod chunks).  A V^T row holds 8 chunks (128 B, half the banks) and is
+// read through rho, whose 16 rows differ in row bits 0..2 and 4: position c ^ f(r) with f built
+// from bits 1, 2, 4 separates the 8 rows of equal parity, parity itself picks the bank half.
+template <int D>
+__device__ __forceinline__ int k_swz(int row) {
+  // D = 128: a row is all 64 banks, 16 rows need 16 positions; D = 64: a row is half the banks,
+  // parity picks the half and the 8 rows of equal parity need 8 positions
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+__device__ __forceinline__ int v_swz(int row) { return ((row >> 1) & 3) | (((row >> 4) & 1) << 2); }
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// One direct global->LDS load: every lane fetches 16 bytes from its own global address and the
+// wavefront's 64 x 16 B land contiguously at the (wave-uniform) LDS address.  Counted by vmcnt.
+// (The builtin only exists in the device pass; the host pass needs no body.)
+__device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, (lds_void *)lds_dst, 16, 0, 0);
+#endif
+}
+
+
+// ---------------------------------------------------------------------------------------
+// Cooperative tile copies global -> LDS for a workgroup of WAVES wavefronts.  Per-lane byte
+// offsets are computed once (init); every copy then costs only a wave-uniform base pointer.
+// ---------------------------------------------------------------------------------------
+
+// ROWS x D bf16 tile of a row-major [L][*] tensor (row pitch sL elements), rows past L - 1
+// re-read row L - 1 (they are masked by the caller).  LDS image: unpadded rows, k_swz swizzle.
+template <int ROWS, int D, int WAVES>
+struct RowTileCopy {
+  static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
+  static constexpr int kInstr = ROWS * kChunks / 64 / WAVES;  // wave instructions per copy
+  uint32_t off[kInstr];
+  int wave, lane;
+  int64_t pitch_bytes;
+
+  __device__ __forceinline__ void init(int wave_, int lane_, int64_t sL) {
+    wave = wave_; lane = lane_; pitch_bytes = sL * 2;
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int row = (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
+      const int pos = lane % kChunks;
+      off[i] = (uint32_t)(row * pitch_bytes + ((pos ^ k_swz<D>(row)) * 16));
+    }
+  }
+  // copy rows [row0, row0 + ROWS) of `tensor` (slab base) into `stage`
+  __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tensor, int row0, int L) const {
+    const char *base = reinterpret_cast<const char *>(tensor) + (int64_t)row0 * pitch_bytes;
+    const int lim = L - 1 - row0;   // last valid row of the tile
+    if (lim >= ROWS - 1) {
+#pragma unroll
+      for (int i = 0; i < kInstr; ++i) lds_dma16(base + off[i], stage + (wave * kInstr + i) * 512);
+    } else {
+#pragma unroll
+      for (int i = 0; i < kInstr; ++i) {
+        const int row = (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
+        const char *src = base + off[i];
+        if (row > lim) src -= (int64_t)(row - lim) * pitch_bytes;
+        lds_dma16(src, stage + (wave * kInstr + i) * 512);
+      }
+    }
+  }
+};
+
+// D x 64 slice (columns [col0, col0 + 64)) of a transposed tile stored as [D][BLK] bf16.
+// LDS image: [D][64], v_swz swizzle.
+template <int BLK, int D, int WAVES>
+struct ColTileCopy {
+  static constexpr int kInstr = D * 8 / 64 / WAVES;
+  uint32_t off[kInstr];
+  int wave;
+
+  __device__ __forceinline__ void init(int wave_, int lane) {
+    wave = wave_;
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int row = (wave * kInstr + i) * 8 + lane / 8;
+      off[i] = (uint32_t)((row * BLK + (((lane % 8) ^ v_swz(row)) * 8)) * 2);
+    }
+  }
+  __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tile, int col0) const {
+    const char *base = reinterpret_cast<const char *>(tile + col0);
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) lds_dma16(base + off[i], stage + (wave * kInstr + i) * 512);
+  }
+};
+
+// LDS address (elements) of the A fragment "row r, 16-byte chunk c" in the two images
+template <int D>
+__device__ __forceinline__ int row_tile_elem(int r, int c) { return r * D + ((c ^ k_swz<D>(r)) * 8); }
+__device__ __forceinline__ int col_tile_elem(int r, int c) { return r * 64 + ((c ^ v_swz(r)) * 8); }
+
+}  // namespace asa
