@@ -8,11 +8,11 @@
 //                    online soft-max need a single cross-lane exchange;
 //   O^T += V^T P^T   the accumulator of S^T, rounded to bf16, already IS the B operand of
 //                    this product, provided the rows of K are read in the permuted order
-//                    kappa below; V is consumed from a [d][L] copy so that both LDS
-//                    operand reads are 16-byte loads.
-// K and V^T tiles go through LDS with 16 bytes of row padding (conflict-free b128 reads).
-#include <type_traits>
-
+//                    kappa; V is consumed from a per-block transposed copy so that both
+//                    LDS operand reads are 16-byte loads.
+// A key block is walked in steps of 64 keys.  The K rows and the V^T slice of a step are copied
+// straight from global memory into LDS (no register staging) with an XOR swizzle of 16-byte
+// chunks instead of row padding, which keeps the 16-byte fragment reads conflict-free.
 #include "asa_common.hpp"
 #include "asa_tiles.hpp"
 
@@ -90,204 +90,119 @@ struct FwdCfg {
   static constexpr int kSub = BLK / kKT;           // steps per key block
   static constexpr int kKElems = kKT * D;          // one K stage:   [64 keys][D]  (unpadded)
   static constexpr int kVElems = D * kKT;          // one V^T stage: [D][64 keys]  (unpadded)
-  static constexpr int kLdsBytes = 2 * (kKElems + kVElems) * 2;
-  // direct-to-LDS copies move 1 KB (64 lanes x 16 B) per wavefront instruction
-  static constexpr int kKInstr = kKElems * 2 / 1024 / kWaves;
-  static constexpr int kVInstr = kVElems * 2 / 1024 / kWaves;
-  static constexpr int kKChunkBits = (D == 128) ? 4 : 3;   // log2(16-byte chunks per K row)
 };
 
 // The running maximum (and with it O and the row sum) is rescaled only on steps where some row
 // of the wavefront actually found a larger logit; on all other steps the factor would be 1.
 // The maximum is never allowed to lag behind: a row dominated by one key then has that key's
 // probability equal to exactly 1, free of bf16 rounding, which the backward's Delta relies on.
-
-template <int BLK, int D>
+//
+// PREFETCH = false: one LDS stage (32 KB at d = 128); the copies of a step are waited for right
+// away and the second workgroup on the CU computes meanwhile.  PREFETCH = true: two stages, the
+// next step's tiles are requested before the current step is computed.  Both were measured;
+// the single-stage form is the faster one on MI355X and is the one that is launched.
+template <int BLK, int D, bool PREFETCH>
 __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
   using C = FwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
-  bf16 *ldsK = reinterpret_cast<bf16 *>(smem);          // 2 stages
-  bf16 *ldsV = ldsK + 2 * C::kKElems;                   // 2 stages
+  bf16 *lds = reinterpret_cast<bf16 *>(smem);
+  constexpr int kStage = C::kKElems + C::kVElems;
+  __shared__ int cols[kMaxNb];
 
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
   const int slab = work / a.Nb;
   const int qb = work - slab * a.Nb;
-
   const int tid = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
-  const int lane = tid & 63;
-  const int hl = lane >> 5;  // which 32-lane half
-  const int n = lane & 31;   // query within the wave / A row within an M tile
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, hl = lane >> 5, n = lane & 31;
 
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vts = a.vt + (int64_t)slab * D * a.Lpad;
   const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
   const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
-  const int n_steps = n_tiles * C::kSub;
-
-  // The row's list of kept key blocks goes to LDS once: reading it from global memory inside
-  // the loop would put a vector-memory wait in front of every step, and such a wait also waits
-  // for all direct-to-LDS tile loads issued before it.
-  __shared__ int cols[kMaxNb];
   {
-    const int32_t *gcols = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = gcols[t];
+    const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
+    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = g[t];
   }
-  __syncthreads();
-
   const int qrow = qb * BLK + wave * 32 + n;
   const bool qvalid = qrow < a.L;
   const int qrow_c = qvalid ? qrow : a.L - 1;
-
-  // Q^T as the B operand of S^T: lane (hl, n) holds Q[qrow][16s + 8hl .. +8]
   bf16x8 qreg[D / 16];
 #pragma unroll
   for (int s = 0; s < D / 16; ++s)
     qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + (int64_t)qrow_c * a.tq.sL + 16 * s + 8 * hl);
-
   f32x16 oacc[D / 32];
 #pragma unroll
   for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[dm][i] = 0.f;
-  float m_run = -INFINITY;  // running maximum, log2 domain
-  float l_run = 0.f;        // running sum of this lane half, relative to m_run
+  float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale_log2e;
 
-  // ---- producers: this lane's share of a K stage / V^T stage, fetched straight into LDS.
-  // Per-lane byte offsets are fixed for the whole kernel; per step only a wave-uniform base
-  // pointer changes, so a load costs no vector ALU work.
-  constexpr int KCH = D / 8;   // chunks per K row
-  uint32_t k_off[C::kKInstr];  // byte offset of my chunk inside a K step, per instruction
-  uint32_t v_off[C::kVInstr];
-#pragma unroll
-  for (int i = 0; i < C::kKInstr; ++i) {
-    const int seg = wave * C::kKInstr + i;            // 1 KB LDS segment = 64 chunks
-    const int row = seg * (64 / KCH) + lane / KCH;    // key row inside the stage
-    const int pos = lane % KCH;                       // chunk position inside the row
-    k_off[i] = (uint32_t)(((int64_t)row * a.tk.sL + ((pos ^ k_swz<D>(row)) * 8)) * 2);
-  }
-#pragma unroll
-  for (int i = 0; i < C::kVInstr; ++i) {
-    const int seg = wave * C::kVInstr + i;
-    const int row = seg * 8 + lane / 8;               // channel row inside the stage
-    v_off[i] = (uint32_t)((row * BLK + (((lane % 8) ^ v_swz(row)) * 8)) * 2);
-  }
-  auto fetch_k = [&](int step, int stage_idx) __attribute__((always_inline)) {
-    const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kKT;
-    bf16 *stage = ldsK + stage_idx * C::kKElems;
-    const char *base = reinterpret_cast<const char *>(ks + (int64_t)key0 * a.tk.sL);
-    const int lim = a.L - 1 - key0;                    // last valid row of this step
-    if (lim >= C::kKT - 1) {
-#pragma unroll
-      for (int i = 0; i < C::kKInstr; ++i)
-        lds_dma16(base + k_off[i], stage + (wave * C::kKInstr + i) * 512);
-    } else {                                           // tail block: re-read the last real row
-#pragma unroll
-      for (int i = 0; i < C::kKInstr; ++i) {
-        const char *src = base + k_off[i];
-        const int row = (wave * C::kKInstr + i) * (64 / KCH) + lane / KCH;
-        if (row > lim) src -= (int64_t)(row - lim) * a.tk.sL * 2;
-        lds_dma16(src, stage + (wave * C::kKInstr + i) * 512);
-      }
-    }
-  };
-  auto fetch_v = [&](int step, int stage_idx) __attribute__((always_inline)) {
-    const char *vtile = reinterpret_cast<const char *>(
-        vts + (int64_t)cols[step / C::kSub] * D * BLK + (step % C::kSub) * C::kKT);
-    bf16 *stage = ldsV + stage_idx * C::kVElems;
-#pragma unroll
-    for (int i = 0; i < C::kVInstr; ++i)
-      lds_dma16(vtile + v_off[i], stage + (wave * C::kVInstr + i) * 512);
-  };
-
-  // ---- consumers: LDS addresses of this lane's MFMA A fragments (stage 0, M tile 0)
-  // K fragment of k-step s: row kappa(n), chunk (2s + hl) ^ swizzle = (2s) ^ (hl ^ swizzle)
-  const int kx = (hl ^ k_swz<D>(kappa(n))) * 8;
-  const bf16 *k_frag[D / 16];
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) k_frag[s] = ldsK + kappa(n) * D + ((16 * s) ^ kx);
-  // V^T fragment of 16-key step t: row rho(n), chunk (2t + hl) ^ swizzle
-  const int vx = (hl ^ v_swz(rho(n))) * 8;
-  const bf16 *v_frag[C::kKT / 16];
-#pragma unroll
-  for (int t = 0; t < C::kKT / 16; ++t) v_frag[t] = ldsV + rho(n) * C::kKT + ((16 * t) ^ vx);
-
-  constexpr int NS = (C::kKT / 32) * (D / 16);   // MFMAs of one S^T step   (16 at D = 128)
-  constexpr int NP = (C::kKT / 16) * (D / 32);   // MFMAs of one P V step   (16 at D = 128)
-  constexpr int NE = (C::kKT / 32) * 8;          // probability pairs per lane and step (16)
+  RowTileCopy<C::kKT, D, C::kWaves> copy_k;
+  ColTileCopy<BLK, D, C::kWaves> copy_v;
+  copy_k.init(wave, lane, a.tk.sL);
+  copy_v.init(wave, lane);
+  const int kr = kappa(n), cr = rho(n);
+  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  // row maximum (log2 domain, both lane halves merged) of a finished S^T step
-  auto row_max = [&](const f32x16 (&sv)[C::kKT / 32]) __attribute__((always_inline)) {
-    float mx = -INFINITY;
-#pragma unroll
-    for (int mt = 0; mt < C::kKT / 32; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sv[mt][i]);
-    return fmaxf(mx, swap_halves(mx)) * c;
+  const int n_steps = n_tiles * C::kSub;
+  auto fetch = [&](int step, int stage) __attribute__((always_inline)) {
+    const int j = cols[step / C::kSub];
+    const int sub = step % C::kSub;
+    bf16 *Kd = lds + stage * kStage;
+    copy_k.issue(Kd, ks, j * BLK + sub * C::kKT, a.L);
+    copy_v.issue(Kd + C::kKElems, vts + (int64_t)j * D * BLK, sub * C::kKT);
   };
-  // keys >= L do not exist (partial last key block)
-  auto mask_tail = [&](int step, f32x16 (&sv)[C::kKT / 32]) __attribute__((always_inline)) {
+  __syncthreads();   // cols[] is complete
+  if (PREFETCH && n_steps > 0) fetch(0, 0);
+  for (int step = 0; step < n_steps; ++step) {
+    const int stage = PREFETCH ? (step & 1) : 0;
+    if (PREFETCH) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // my copies of this step have landed
+      __syncthreads();                      // everyone's have; the other stage is free
+      if (step + 1 < n_steps) fetch(step + 1, stage ^ 1);
+    } else {
+      __syncthreads();
+      fetch(step, 0);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    }
+    const bf16 *Ks = lds + stage * kStage;
+    const bf16 *Vs = Ks + C::kKElems;
     const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kKT;
+    f32x16 sacc[C::kKT / 32];
+#pragma unroll
+    for (int mt = 0; mt < C::kKT / 32; ++mt) {
+      const bf16 *krow = Ks + (mt * 32 + kr) * D;
+      sacc[mt] = zero16;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) {
+        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(krow + ((16 * s) ^ kx));
+        sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc[mt], 0, 0, 0);
+      }
+    }
     if (key0 + C::kKT > a.L) {
 #pragma unroll
       for (int mt = 0; mt < C::kKT / 32; ++mt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           int key = key0 + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
-          if (key >= a.L) sv[mt][i] = -INFINITY;
+          if (key >= a.L) sacc[mt][i] = -INFINITY;
         }
     }
-  };
-
-  if (n_steps > 0) {
-    fetch_k(0, 0);
-    fetch_v(0, 0);
-    if (n_steps > 1) fetch_k(1, 1);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): my direct loads have landed
-  __syncthreads();
-
-  // S^T of step 0 (not overlapped with anything) and its row maximum
-  f32x16 s_a[C::kKT / 32], s_b[C::kKT / 32];
-  float mx_cur = -INFINITY;
-  if (n_steps > 0) {
+    float mx = -INFINITY;
 #pragma unroll
-    for (int mt = 0; mt < C::kKT / 32; ++mt) {
-      s_a[mt] = zero16;
+    for (int mt = 0; mt < C::kKT / 32; ++mt)
 #pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(k_frag[s] + mt * 32 * D);
-        s_a[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], s_a[mt], 0, 0, 0);
-      }
-    }
-    mask_tail(0, s_a);
-    mx_cur = row_max(s_a);
-  }
-
-  // One pipeline step, software-pipelined across steps and scheduled by hand in "slices" of
-  // one MFMA each, so that the matrix pipe and the VALU run side by side within a wavefront:
-  //   phase 1: S^T of step+1 (MFMA)  ||  exp2 / sum / bf16 packing of step (VALU)
-  //   phase 2: P V of step   (MFMA)  ||  nothing much; then the row maximum of step+1
-  // LDS fragments are requested two slices ahead of the MFMA that consumes them.  PAR is the
-  // parity of `step` (the loop is unrolled by two so that LDS stage offsets are immediates
-  // and the two S^T register sets swap roles without copies).
-  auto body = [&](auto par_tag, int step, f32x16 (&s_cur)[C::kKT / 32],
-                  f32x16 (&s_nxt)[C::kKT / 32]) __attribute__((always_inline)) {
-    constexpr int PAR = decltype(par_tag)::value;
-    // everyone is past S(step) (reads K stage PAR) and past PV(step-1) (V stage 1-PAR), and
-    // every wave's loads of K(step+1), V(step) have landed
-    __syncthreads();
-    if (step + 2 < n_steps) fetch_k(step + 2, PAR);
-    if (step + 1 < n_steps) fetch_v(step + 1, 1 - PAR);
-
-    // ---- raise the running maximum only if some row of the wavefront found a larger logit
-    if (__any(mx_cur > m_run)) {
-      const float m_new = fmaxf(m_run, mx_cur);
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[mt][i]);
+    mx = fmaxf(mx, swap_halves(mx)) * c;
+    if (__any(mx > m_run)) {
+      const float m_new = fmaxf(m_run, mx);
       const float alpha = fast_exp2(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
       m_run = m_new;
       l_run *= alpha;
@@ -297,76 +212,32 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
         for (int i = 0; i < 16; ++i) oacc[dm][i] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-
-    constexpr int k_stage = (1 - PAR) * C::kKElems;   // K(step+1)
-    constexpr int v_stage = PAR * C::kVElems;         // V(step)
-    uint32_t pb[NE];
     float lsum = 0.f;
-
-    // ---- phase 1
-    __builtin_amdgcn_sched_barrier(0);
-    {
-      bf16x8 kf[3];
-      auto kread = [&](int sl) __attribute__((always_inline)) {
-        return *reinterpret_cast<const bf16x8 *>(k_frag[sl / (C::kKT / 32)] + k_stage +
-                                                 (sl % (C::kKT / 32)) * 32 * D);
-      };
-      kf[0] = kread(0);
-      kf[1] = kread(1);
 #pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        if (sl + 2 < NS) kf[(sl + 2) % 3] = kread(sl + 2);
-        const int mt = sl % (C::kKT / 32), ks = sl / (C::kKT / 32);
-        s_nxt[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sl % 3], qreg[ks],
-                                                            ks == 0 ? zero16 : s_nxt[mt], 0, 0, 0);
-        // VALU share of this slice: NE pairs spread over NS slices
+    for (int mt = 0; mt < C::kKT / 32; ++mt) {
+      uint32_t pb[8];
 #pragma unroll
-        for (int e = sl * NE / NS; e < (sl + 1) * NE / NS; ++e) {
-          const int emt = e / 8, ei = (e % 8) * 2;
-          const float p0 = fast_exp2(fmaf(s_cur[emt][ei], c, -m_use));
-          const float p1 = fast_exp2(fmaf(s_cur[emt][ei + 1], c, -m_use));
-          lsum += p0 + p1;   // unrounded: LSE must not inherit a dominant key's bf16 rounding
-          pb[e] = pack_bf16x2(p0, p1);
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = fast_exp2(fmaf(sacc[mt][i], c, -m_use));
+        const float p1 = fast_exp2(fmaf(sacc[mt][i + 1], c, -m_use));
+        lsum += p0 + p1;
+        pb[i >> 1] = pack_bf16x2(p0, p1);
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        uint4 praw = make_uint4(pb[4 * tt], pb[4 * tt + 1], pb[4 * tt + 2], pb[4 * tt + 3]);
+        bf16x8 pf = *reinterpret_cast<bf16x8 *>(&praw);
+#pragma unroll
+        for (int dm = 0; dm < D / 32; ++dm) {
+          bf16x8 va = *reinterpret_cast<const bf16x8 *>(Vs + (dm * 32 + cr) * C::kKT +
+                                                        ((16 * (2 * mt + tt)) ^ cx));
+          oacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf, oacc[dm], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
     l_run += lsum;
-
-    // ---- phase 2
-    {
-      bf16x8 vf[3];
-      auto vread = [&](int sl) __attribute__((always_inline)) {
-        return *reinterpret_cast<const bf16x8 *>(v_frag[sl / (D / 32)] + v_stage +
-                                                 (sl % (D / 32)) * 32 * C::kKT);
-      };
-      vf[0] = vread(0);
-      vf[1] = vread(1);
-#pragma unroll
-      for (int sl = 0; sl < NP; ++sl) {
-        if (sl + 2 < NP) vf[(sl + 2) % 3] = vread(sl + 2);
-        const int dm = sl % (D / 32), t = sl / (D / 32);
-        uint4 praw = make_uint4(pb[4 * t], pb[4 * t + 1], pb[4 * t + 2], pb[4 * t + 3]);
-        oacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            vf[sl % 3], *reinterpret_cast<bf16x8 *>(&praw), oacc[dm], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // row maximum of the next step (its S^T finished during phase 1; past the last step the
-    // values come from a stale stage and are dropped)
-    if (step + 1 < n_steps) {
-      mask_tail(step + 1, s_nxt);
-      mx_cur = row_max(s_nxt);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0) before the barrier that publishes my loads
-  };
-
-  for (int step = 0; step < n_steps; step += 2) {
-    body(std::integral_constant<int, 0>{}, step, s_a, s_b);
-    if (step + 1 < n_steps) body(std::integral_constant<int, 1>{}, step + 1, s_b, s_a);
   }
 
-  // ---- epilogue
   const float l_tot = l_run + swap_halves(l_run);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (qvalid) {
@@ -380,7 +251,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
         const float v0 = oacc[dm][i] * inv, v1 = oacc[dm][i + 1] * inv;
         const uint32_t pk = pack_bf16x2(v0, v1);
         w[i >> 1] = pk;
-        // what the rounding to bf16 dropped, itself rounded to bf16
         r[i >> 1] = pack_bf16x2(v0 - bf16_bits_to_float(pk & 0xffffu),
                                 v1 - bf16_bits_to_float(pk >> 16));
       }
@@ -402,15 +272,16 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
 template <int BLK, int D>
 static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   using C = FwdCfg<BLK, D>;
+  constexpr int lds = (C::kKElems + C::kVElems) * 2;   // one stage
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   int grid = xcd_grid(a.n_slabs * a.Nb);
-  hipLaunchKernelGGL((fwd_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kLdsBytes, st, a);
+  hipLaunchKernelGGL((fwd_kernel<BLK, D, false>), dim3(grid), dim3(C::kThreads), lds, st, a);
   return hipGetLastError();
 }
 
