@@ -13,6 +13,10 @@
 // A key block is walked in steps of 64 keys.  The K rows and the V^T slice of a step are copied
 // straight from global memory into LDS (no register staging) with an XOR swizzle of 16-byte
 // chunks instead of row padding, which keeps the 16-byte fragment reads conflict-free.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "asa_common.hpp"
 #include "asa_tiles.hpp"
 
@@ -269,6 +273,438 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Ping-pong forward.  The workgroup has two groups of BLK/32 wavefronts that own the SAME
+// query rows; group g processes the 64-key steps s with s mod 2 = g and keeps its own
+// (maximum, row sum, O) partial, merged once at the end.  Time is cut into phases separated by
+// workgroup barriers.  In phase p group (p mod 2) is in its MATRIX phase -- P V of step p-2, then
+// S^T of step p -- while the other group is in its VECTOR phase -- soft-max of step p-1.  The
+// two groups share every SIMD pairwise (wavefronts w and w + BLK/32), so at any time one
+// wavefront per SIMD feeds the matrix pipe and the other the vector ALU.
+//
+// What was measured on MI355X and shaped this kernel:
+//  * A wavefront whose next instruction is an MFMA that waits for the matrix pipe keeps the
+//    SIMD's issue slot: with equal priorities the older wavefront starves the other one's vector
+//    instructions completely.  With the VECTOR wavefront at the higher priority both run: the
+//    MFMA stream loses nothing and the vector stream runs at ~80 % of its stand-alone rate.
+//  * One 64 x 16 B direct-to-LDS load occupies the issuing wavefront for 65..90 cycles (much
+//    more on a wavefront of lower priority).  The copies are therefore requested by the
+//    vector group (it has the priority and no MFMA stream to hold up), a few at a time between
+//    blocks of soft-max arithmetic.
+//  * Scalar bookkeeping shows up directly as idle matrix time (the scalar unit is shared):
+//    the phase loop is unrolled so that p mod 4 is a compile-time constant, every LDS address
+//    is an immediate, and the column list is turned once into byte offsets of the K and V^T
+//    tiles (LDS tables padded by repeats of the last entry, so copies past the last step need
+//    no clamping).
+// Tiles: four LDS buffers each for K and V^T steps, buffer = step mod 4.  Phase p requests K
+// of step p+3 and V of step p+1; both buffers were last read in phase p-1.
+// ---------------------------------------------------------------------------------------
+template <int BLK, int D>
+struct PpCfg {
+  static constexpr int kGroupWaves = BLK / 32;
+  static constexpr int kWaves = 2 * kGroupWaves;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kKT = 64;
+  static constexpr int kSub = BLK / kKT;
+  static constexpr int kKElems = kKT * D;
+  static constexpr int kVElems = D * kKT;
+  static constexpr int kStages = 4;
+  static constexpr int kTabPad = 8;
+  static constexpr int kLdsBytes = kStages * (kKElems + kVElems) * 2;
+};
+
+template <int N>
+using Int = std::integral_constant<int, N>;
+
+template <int BLK, int D>
+__global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
+  using C = PpCfg<BLK, D>;
+  extern __shared__ __align__(1024) unsigned char smem[];
+  bf16 *ldsK = reinterpret_cast<bf16 *>(smem);
+  bf16 *ldsV = ldsK + C::kStages * C::kKElems;
+  const uint32_t ldsK_addr = ASA_LDS_ADDR_OF(smem);                       // for the copies
+  const uint32_t ldsV_addr = ldsK_addr + C::kStages * C::kKElems * 2;
+  __shared__ uint32_t tabK[kMaxNb + C::kTabPad], tabV[kMaxNb + C::kTabPad];
+
+  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  if (work < 0) return;
+  const int slab = work / a.Nb;
+  const int qb = work - slab * a.Nb;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave / C::kGroupWaves;       // 0 or 1
+  const int wq = wave % C::kGroupWaves;        // which 32 query rows
+  const int lane = tid & 63, hl = lane >> 5, n = lane & 31;
+
+  const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
+  const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
+  const bf16 *vts = a.vt + (int64_t)slab * D * a.Lpad;
+  const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
+  const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  const int n_steps = n_tiles * C::kSub;
+  const uint32_t pitch_bytes = (uint32_t)a.tk.sL * 2u;
+  const uint32_t k_tile_bytes = BLK * pitch_bytes;     // host checked: Nb * this < 2^32
+  constexpr uint32_t v_tile_bytes = D * BLK * 2;
+  {
+    const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
+    for (int t = tid; t < n_tiles + C::kTabPad; t += C::kThreads) {
+      const int tc = t < n_tiles ? t : n_tiles - 1;
+      const uint32_t j = n_tiles > 0 ? (uint32_t)g[tc] : 0u;
+      tabK[t] = j * k_tile_bytes;
+      tabV[t] = j * v_tile_bytes;
+    }
+  }
+  const int qrow = qb * BLK + wq * 32 + n;
+  const bool qvalid = qrow < a.L;
+  const int qrow_c = qvalid ? qrow : a.L - 1;
+  bf16x8 qreg[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s)
+    qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + (int64_t)qrow_c * a.tq.sL + 16 * s + 8 * hl);
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[dm][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = a.scale_log2e;
+
+  // The copies of a phase are requested by its VECTOR group (wavefront wq copies a quarter
+  // -- BLK = 64: half -- of each tile).
+  RowTileCopy<C::kKT, D, C::kGroupWaves> copy_k;
+  ColTileCopy<BLK, D, C::kGroupWaves> copy_v;
+  copy_k.init(wq, lane, a.tk.sL);
+  copy_v.init(wq, lane);
+  constexpr int kInstrK = RowTileCopy<C::kKT, D, C::kGroupWaves>::kInstr;
+  constexpr int kBatchInstr = kInstrK + ColTileCopy<BLK, D, C::kGroupWaves>::kInstr;
+  static_assert(kBatchInstr == 4 || kBatchInstr == 8 || kBatchInstr == 16, "unexpected copy size");
+  const int kr = kappa(n), cr = rho(n);
+  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // Only the last key block can be ragged.  Per 64-key half of a block: the table entry that
+  // means "this step reaches past L" (or an impossible value if that half of the last block is
+  // complete).
+  const int last_row0 = (a.Nb - 1) * BLK;
+  uint32_t k_tail[C::kSub], v_tail[C::kSub];
+  const char *k_base[C::kSub], *v_base[C::kSub];
+#pragma unroll
+  for (int sb = 0; sb < C::kSub; ++sb) {
+    const bool ragged = last_row0 + sb * C::kKT + C::kKT > a.L;
+    k_tail[sb] = ragged ? (uint32_t)(a.Nb - 1) * k_tile_bytes : 0xFFFFFFFFu;
+    v_tail[sb] = ragged ? (uint32_t)(a.Nb - 1) * v_tile_bytes : 0xFFFFFFFFu;
+    k_base[sb] = reinterpret_cast<const char *>(ks) + (int64_t)sb * C::kKT * pitch_bytes;
+    v_base[sb] = reinterpret_cast<const char *>(vts) + sb * C::kKT * 2;
+  }
+
+  __syncthreads();   // tables complete
+  // Before phase 0: K of steps 0, 1, 2 and V of step 0 (group 0: K(0), K(2); group 1: K(1),
+  // V(0)).  Any of the K tiles may be the ragged one.
+  {
+    const char *kb = reinterpret_cast<const char *>(ks);
+    auto k_step = [&](int step) __attribute__((always_inline)) {
+      const int j = (int)(__builtin_amdgcn_readfirstlane(tabV[step / C::kSub]) / v_tile_bytes);
+      const int r = j * BLK + (step % C::kSub) * C::kKT;
+      copy_k.issue_at_ragged(ldsK_addr + step * C::kKElems * 2, kb + (int64_t)r * pitch_bytes, a.L - 1 - r);
+    };
+    if (grp == 0) {
+      k_step(0);
+      k_step(2);
+    } else {
+      k_step(1);
+      copy_v.issue_at(ldsV_addr, v_base[0] + __builtin_amdgcn_readfirstlane(tabV[0]));
+    }
+  }
+  // Table entries of the copies of phase 0 (K of step 3, V of step 1) and the V entries of the
+  // three phases before, which tell the soft-max whether its step is the ragged one.
+  uint32_t ek_next = tabK[3 / C::kSub], ev_next = tabV[1 / C::kSub];
+  uint32_t ek_cur = 0, ev_cur = tabV[0], ev_last = 0xFFFFFFFFu, ev_older = 0xFFFFFFFFu;
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+
+  f32x16 sacc[C::kKT / 32];
+  uint32_t pb[(C::kKT / 32) * 8];
+#pragma unroll
+  for (int mt = 0; mt < C::kKT / 32; ++mt) sacc[mt] = zero16;
+#pragma unroll
+  for (int e = 0; e < (C::kKT / 32) * 8; ++e) pb[e] = 0;
+
+  // Start of phase p (R = p mod 4).  The vector group of phase p requests, spread over that
+  // phase, K of step p+3 and V of step p+1 (their buffers were last read in phase p-1).  Data
+  // needed in phase p -- K(p), V(p-2) -- was requested during phase p-3 by the group that has
+  // just finished phase p-1's vector work: "all of my copies but the newest batch have landed"
+  // on every wavefront, followed by the barrier, makes it visible to all.
+  auto phase_sync = [&](int p) __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (kBatchInstr == 4) __builtin_amdgcn_s_waitcnt(0x0F74);
+    else if (kBatchInstr == 8) __builtin_amdgcn_s_waitcnt(0x0F78);
+    else __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): low bits 0, high bits (15:14) 1
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    ek_cur = __builtin_amdgcn_readfirstlane(ek_next);
+    ev_older = ev_last;
+    ev_last = ev_cur;
+    ev_cur = __builtin_amdgcn_readfirstlane(ev_next);
+    ek_next = tabK[(p + 4) / C::kSub];
+    ev_next = tabV[(p + 2) / C::kSub];
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // The K copy of this phase: wave-uniform base and per-lane offsets.  Normally the offsets are
+  // the tile's own; for the one ragged step they are bent back to the last row (rare branch).
+  const char *kdma_base = nullptr;
+  uint32_t kdma_off[kInstrK];
+  auto dma_prepare = [&](auto r_tag) __attribute__((always_inline)) {
+    constexpr int sb = (decltype(r_tag)::value + 1) % C::kSub;
+    kdma_base = k_base[sb] + ek_cur;
+#pragma unroll
+    for (int i = 0; i < kInstrK; ++i) kdma_off[i] = copy_k.off[i];
+    if (ek_cur == k_tail[sb]) {
+      int lim = a.L - 1 - (last_row0 + sb * C::kKT);
+      if (lim < 0) {
+        kdma_base += (int64_t)lim * pitch_bytes;
+        lim = 0;
+      }
+#pragma unroll
+      for (int i = 0; i < kInstrK; ++i) {
+        const int row = copy_k.row_of(i);
+        if (row > lim) kdma_off[i] -= (uint32_t)(row - lim) * pitch_bytes;
+      }
+    }
+  };
+  // i-th load of this wavefront's share of the batch of phase R: K of step R+3, V of step R+1
+  auto dma_one = [&](auto r_tag, int i) __attribute__((always_inline)) {
+    constexpr int R = decltype(r_tag)::value;
+    constexpr int sb = (R + 1) % C::kSub;
+    if (i < kInstrK)
+      lds_dma16_sv(kdma_base, kdma_off[i], ldsK_addr + ((R + 3) & 3) * C::kKElems * 2 + copy_k.lds_chunk(i));
+    else
+      copy_v.issue_one_at(i - kInstrK, ldsV_addr + ((R + 1) & 3) * C::kVElems * 2, v_base[sb] + ev_cur);
+  };
+  auto dma_all = [&](auto r_tag) __attribute__((always_inline)) {
+    dma_prepare(r_tag);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // MATRIX phase p (R = p mod 4): P V of step p-2 followed by S^T of step p.  One wavefront
+  // per SIMD runs it at a time, so the LDS fragment reads are software-pipelined kDepth tile
+  // products ahead of the MFMA that consumes them.  Runs at the low priority.
+  constexpr int kNPv = (C::kKT / 16) * (D / 32);
+  constexpr int kNS = (D / 16) * (C::kKT / 32);
+  constexpr int kDepth = 6, kRing = kDepth + 1;
+  auto do_matrix = [&](auto r_tag, auto with_pv, auto with_s) __attribute__((always_inline)) {
+    constexpr int R = decltype(r_tag)::value;
+    constexpr bool kPv = decltype(with_pv)::value, kS = decltype(with_s)::value;
+    constexpr int n0 = kPv ? 0 : kNPv, n1 = kS ? kNPv + kNS : kNPv;
+    const bf16 *Vs = ldsV + ((R + 2) & 3) * C::kVElems;
+    const bf16 *Ks = ldsK + R * C::kKElems;
+    bf16x8 ring[kRing];
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+    for (int i = n0; i < n1 + kDepth; ++i) {
+      if (i < n1) {
+        if (i < kNPv) {
+          const int t = i / (D / 32), dm = i % (D / 32);
+          ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Vs + (dm * 32 + cr) * C::kKT + ((16 * t) ^ cx));
+        } else {
+          const int e = i - kNPv, sk = e / (C::kKT / 32), mt = e % (C::kKT / 32);
+          ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Ks + (mt * 32 + kr) * D + ((16 * sk) ^ kx));
+        }
+      }
+      const int c_i = i - kDepth;
+      if (c_i >= n0) {
+        if (c_i < kNPv) {
+          const int t = c_i / (D / 32), dm = c_i % (D / 32);
+          const u32x4 praw = {pb[4 * t], pb[4 * t + 1], pb[4 * t + 2], pb[4 * t + 3]};
+          oacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[c_i % kRing], __builtin_bit_cast(bf16x8, praw),
+                                                            oacc[dm], 0, 0, 0);
+        } else {
+          const int e = c_i - kNPv, sk = e / (C::kKT / 32), mt = e % (C::kKT / 32);
+          sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[c_i % kRing], qreg[sk],
+                                                            sk == 0 ? zero16 : sacc[mt], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_setprio(3);
+  };
+
+  // VECTOR phase p: online soft-max of step p-1 (RX = that step mod 4), whose S^T is in sacc;
+  // leaves bf16 P in pb.  Runs at the high priority and requests the phase's copies, an eighth
+  // of them at a time between blocks of arithmetic.
+  auto do_x = [&](auto rx_tag) __attribute__((always_inline)) {
+    constexpr int sb = decltype(rx_tag)::value % C::kSub;
+    const Int<(decltype(rx_tag)::value + 1) & 3> r_tag{};   // the phase this runs in
+    constexpr int kPortion = kBatchInstr / 8 > 0 ? kBatchInstr / 8 : 1;
+    int next_copy = 0;
+    auto request = [&](int n_instr) __attribute__((always_inline)) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < n_instr; ++e)
+        if (next_copy < kBatchInstr) dma_one(r_tag, next_copy++);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    __builtin_amdgcn_s_setprio(3);
+    dma_prepare(r_tag);
+    if (ev_older == v_tail[sb]) {
+      const int key0 = last_row0 + sb * C::kKT;
+#pragma unroll
+      for (int mt = 0; mt < C::kKT / 32; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          int key = key0 + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
+          if (key >= a.L) sacc[mt][i] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < C::kKT / 32; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[mt][i]);
+    request(kPortion);
+    mx = fmaxf(mx, swap_halves(mx)) * c;
+    if (__any(mx > m_run)) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = fast_exp2(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[dm][i] *= alpha;
+    }
+    request(kPortion);
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    float lsum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < C::kKT / 32; ++mt) {
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        if (i == 4 || i == 8 || i == 12) request(kPortion);
+        const float p0 = fast_exp2(fmaf(sacc[mt][i], c, -m_use));
+        const float p1 = fast_exp2(fmaf(sacc[mt][i + 1], c, -m_use));
+        lsum += p0 + p1;
+        pb[mt * 8 + (i >> 1)] = pack_bf16x2(p0, p1);
+      }
+    }
+    l_run += lsum;
+    request(kBatchInstr);   // whatever is left
+  };
+
+  const std::true_type yes{};
+  const std::false_type no{};
+  // Group g owns steps g, g+2, ...; its k-th own step is step (= phase) 2k + g.
+  auto run_group = [&](auto g_tag) __attribute__((always_inline)) {
+    constexpr int G = decltype(g_tag)::value;
+    using R0 = Int<G>;
+    using R1 = Int<(G + 1) & 3>;
+    using R2 = Int<(G + 2) & 3>;
+    using R3 = Int<(G + 3) & 3>;
+    int p = 0;
+    if (G == 1) { phase_sync(p); dma_all(Int<0>{}); ++p; }   // group 0's matrix slot, my copies
+    const int n_own = n_steps > G ? (n_steps - G + 1) / 2 : 0;
+    if (n_own > 0) {
+      phase_sync(p); do_matrix(R0{}, no, yes); ++p;
+      phase_sync(p); do_x(R0{}); ++p;
+      int k = 1;
+      for (; k + 1 < n_own; k += 2) {
+        phase_sync(p); do_matrix(R2{}, yes, yes); ++p;
+        phase_sync(p); do_x(R2{}); ++p;
+        phase_sync(p); do_matrix(R0{}, yes, yes); ++p;
+        phase_sync(p); do_x(R0{}); ++p;
+      }
+      if (k < n_own) {
+        phase_sync(p); do_matrix(R2{}, yes, yes); ++p;
+        phase_sync(p); do_x(R2{}); ++p;
+        phase_sync(p); do_matrix(R0{}, yes, no); ++p;
+      } else {
+        phase_sync(p); do_matrix(R2{}, yes, no); ++p;
+      }
+    }
+    // the other group may still have phases to run: keep the barriers and copies in step
+    for (; p < n_steps + 2; ++p) {
+      switch (p & 3) {
+        case 0: phase_sync(p); if (G == 1) dma_all(Int<0>{}); break;
+        case 1: phase_sync(p); if (G == 0) dma_all(Int<1>{}); break;
+        case 2: phase_sync(p); if (G == 1) dma_all(Int<2>{}); break;
+        default: phase_sync(p); if (G == 0) dma_all(Int<3>{}); break;
+      }
+    }
+  };
+  if (grp == 0) run_group(Int<0>{});
+  else run_group(Int<1>{});
+
+  // ---- merge the two groups' partials (group 1 -> LDS -> group 0), then write out
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // stray copies must land before the buffers are reused
+  __syncthreads();
+  f32x4 *xbuf = reinterpret_cast<f32x4 *>(smem);          // [4 * D/32][BLK * 2] f32x4
+  float *xm = reinterpret_cast<float *>(xbuf + 4 * (D / 32) * (BLK * 2));
+  float *xl = xm + BLK * 2;
+  const int slot = wq * 64 + lane;
+  float l_half = l_run + swap_halves(l_run);
+  if (grp == 1) {
+#pragma unroll
+    for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 v = {oacc[dm][4 * q4], oacc[dm][4 * q4 + 1], oacc[dm][4 * q4 + 2], oacc[dm][4 * q4 + 3]};
+        xbuf[(dm * 4 + q4) * (BLK * 2) + slot] = v;
+      }
+    xm[slot] = m_run;
+    xl[slot] = l_half;
+  }
+  __syncthreads();
+  if (grp == 1) return;
+  {
+    const float m_o = xm[slot], l_o = xl[slot];
+    const float m_all = fmaxf(m_run, m_o);
+    const float ms = (m_all == -INFINITY) ? 0.f : m_all;
+    const float fa = fast_exp2(m_run - ms), fb = fast_exp2(m_o - ms);
+    l_half = l_half * fa + l_o * fb;
+#pragma unroll
+    for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 v = xbuf[(dm * 4 + q4) * (BLK * 2) + slot];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) oacc[dm][4 * q4 + e] = oacc[dm][4 * q4 + e] * fa + v[e] * fb;
+      }
+    m_run = m_all;
+  }
+  const float l_tot = l_half;
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (qvalid) {
+    bf16 *os = slab_ptr(a.o, a.to, slab, a.H) + (int64_t)qrow * a.to.sL;
+    bf16 *ls = a.o_lo ? slab_ptr(a.o_lo, a.to, slab, a.H) + (int64_t)qrow * a.to.sL : nullptr;
+#pragma unroll
+    for (int dm = 0; dm < D / 32; ++dm) {
+      uint32_t w[8], r[8];
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float v0 = oacc[dm][i] * inv, v1 = oacc[dm][i + 1] * inv;
+        const uint32_t pk = pack_bf16x2(v0, v1);
+        w[i >> 1] = pk;
+        r[i >> 1] = pack_bf16x2(v0 - bf16_bits_to_float(pk & 0xffffu),
+                                v1 - bf16_bits_to_float(pk >> 16));
+      }
+      uint4 *dst = reinterpret_cast<uint4 *>(os + dm * 32 + 16 * hl);
+      dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+      dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+      if (ls) {
+        uint4 *dl = reinterpret_cast<uint4 *>(ls + dm * 32 + 16 * hl);
+        dl[0] = make_uint4(r[0], r[1], r[2], r[3]);
+        dl[1] = make_uint4(r[4], r[5], r[6], r[7]);
+      }
+    }
+    if (hl == 0)
+      a.lse[(int64_t)slab * a.L + qrow] =
+          l_tot > 0.f ? m_run * 0.69314718055994530942f + __logf(l_tot) : -INFINITY;
+  }
+}
+
 template <int BLK, int D>
 static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   using C = FwdCfg<BLK, D>;
@@ -281,6 +717,18 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
     attr_set = true;
   }
   int grid = xcd_grid(a.n_slabs * a.Nb);
+  // The ping-pong kernel addresses K tiles by 32-bit byte offsets inside a slab; tensors whose
+  // slabs span 4 GiB or more take the single-stage kernel.  (ASA_FWD_PLAIN=1 forces the latter:
+  // used to compare the two.)
+  const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
+  if (fits32 && !getenv("ASA_FWD_PLAIN")) {
+    using P = PpCfg<BLK, D>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((fwd_pp_kernel<BLK, D>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((fwd_kernel<BLK, D, false>), dim3(grid), dim3(C::kThreads), lds, st, a);
   return hipGetLastError();
 }

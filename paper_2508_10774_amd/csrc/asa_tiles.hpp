@@ -48,6 +48,22 @@ __device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
 #endif
 }
 
+// The same load with the address split into a wave-uniform 64-bit base (scalar registers) and
+// a 32-bit per-lane byte offset: stepping to another tile then costs scalar adds only and the
+// per-lane offsets stay 32 bits wide.  The compiler does not see this load: the caller waits
+// with an explicit vmcnt before reading the LDS image, and a kernel that uses this form uses
+// it for all of its direct loads (M0 is written here).
+// lds_byte_addr is the wave-uniform LDS address (lds_addr_of() of the LDS array + offset).
+__device__ __forceinline__ void lds_dma16_sv(const void *uniform_base, uint32_t lane_off,
+                                             uint32_t lds_byte_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(uniform_base), "s"(lds_byte_addr) : "memory");
+#endif
+}
+// LDS byte address of an object that the compiler knows to live in LDS (apply it to the
+// __shared__ array itself, not to a pointer that travelled through generic address space)
+#define ASA_LDS_ADDR_OF(shared_array) ((uint32_t)(uintptr_t)(::asa::lds_void *)(shared_array))
 
 // ---------------------------------------------------------------------------------------
 // Cooperative tile copies global -> LDS for a workgroup of WAVES wavefronts.  Per-lane byte
@@ -71,6 +87,45 @@ struct RowTileCopy {
       const int row = (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
       const int pos = lane % kChunks;
       off[i] = (uint32_t)(row * pitch_bytes + ((pos ^ k_swz<D>(row)) * 16));
+    }
+  }
+  // copy the ROWS complete rows that start at byte address `base` into `stage`
+  // row of the tile that instruction i of this lane copies; byte offset of its 1 KB LDS chunk
+  __device__ __forceinline__ int row_of(int i) const {
+    return (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
+  }
+  __device__ __forceinline__ uint32_t lds_chunk(int i) const { return (wave * kInstr + i) * 1024; }
+  // (the *_at forms take the LDS byte address of the stage)
+  __device__ __forceinline__ void issue_at(uint32_t stage, const char *base) const {
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
+  }
+  // instruction i of that copy alone (a kernel may spread the kInstr loads of a copy over time)
+  __device__ __forceinline__ void issue_one_at(int i, uint32_t stage, const char *base) const {
+    lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
+  }
+  __device__ __forceinline__ void issue_one_at_ragged(int i, uint32_t stage, const char *base, int lim) const {
+    if (lim < 0) {
+      base += (int64_t)lim * pitch_bytes;
+      lim = 0;
+    }
+    const int row = (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
+    const uint32_t o = row > lim ? off[i] - (uint32_t)(row - lim) * (uint32_t)pitch_bytes : off[i];
+    lds_dma16_sv(base, o, stage + (wave * kInstr + i) * 1024);
+  }
+  // the same for a tile whose rows past `lim` (relative to the tile) re-read row `lim`.
+  // lim < 0 (the whole tile lies past the last row) moves the base back to that row first:
+  // the per-lane offsets are unsigned and must not go negative.
+  __device__ __forceinline__ void issue_at_ragged(uint32_t stage, const char *base, int lim) const {
+    if (lim < 0) {
+      base += (int64_t)lim * pitch_bytes;
+      lim = 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int row = (wave * kInstr + i) * (64 / kChunks) + lane / kChunks;
+      const uint32_t o = row > lim ? off[i] - (uint32_t)(row - lim) * (uint32_t)pitch_bytes : off[i];
+      lds_dma16_sv(base, o, stage + (wave * kInstr + i) * 1024);
     }
   }
   // copy rows [row0, row0 + ROWS) of `tensor` (slab base) into `stage`
@@ -112,6 +167,13 @@ struct ColTileCopy {
     const char *base = reinterpret_cast<const char *>(tile + col0);
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) lds_dma16(base + off[i], stage + (wave * kInstr + i) * 512);
+  }
+  __device__ __forceinline__ void issue_at(uint32_t stage, const char *base) const {
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
+  }
+  __device__ __forceinline__ void issue_one_at(int i, uint32_t stage, const char *base) const {
+    lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
   }
 };
 
