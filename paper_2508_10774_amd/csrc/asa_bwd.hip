@@ -152,6 +152,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
 
   const int n_steps = n_tiles * C::kSub;
   for (int step = 0; step < n_steps; ++step) {
+    __builtin_amdgcn_s_setprio(3);
     __syncthreads();   // the previous step's fragments are consumed (and cols[] is written)
     const int j = cols[step / C::kSub];
     const int sub = step % C::kSub;
@@ -164,6 +165,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     const bool tail = key0 + C::kST > a.L;
 #pragma unroll
     for (int mt = 0; mt < C::kST / 32; ++mt) {
+      __builtin_amdgcn_s_setprio(0);
       const bf16 *krow = Ks + (mt * 32 + kr) * D;
       const bf16 *vrow = Vs + (mt * 32 + kr) * D;
       f32x16 sacc = zero16, pacc = zero16;
@@ -175,6 +177,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[s], pacc, 0, 0, 0);
       }
       uint32_t dsb[8];
+      __builtin_amdgcn_s_setprio(3);   // vector work goes ahead of the other workgroup's MFMA stream
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
         float p0 = fast_exp2(fmaf(sacc[i], c, -lse2));
@@ -186,6 +189,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
         }
         dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - delta), p1 * (pacc[i + 1] - delta));
       }
+      __builtin_amdgcn_s_setprio(0);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         uint4 raw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
@@ -288,6 +292,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
 
   const int n_steps = n_tiles * C::kSub;
   for (int step = 0; step < n_steps; ++step) {
+    __builtin_amdgcn_s_setprio(3);
     __syncthreads();
     const int i_blk = rows[step / C::kSub];
     const int sub = step % C::kSub;
@@ -309,6 +314,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     __syncthreads();
 #pragma unroll
     for (int mt = 0; mt < C::kST / 32; ++mt) {
+      __builtin_amdgcn_s_setprio(0);
       const bf16 *qrow = Qs + (mt * 32 + kr) * D;
       const bf16 *grow = Gs + (mt * 32 + kr) * D;
       f32x16 sacc = zero16, pacc = zero16;
@@ -323,6 +329,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
       }
       // accumulator register i of lane half hl is query 32mt + 16(i/8) + 8hl + (i%8)
       uint32_t pb[8], dsb[8];
+      __builtin_amdgcn_s_setprio(3);   // vector work goes ahead of the other workgroup's MFMA stream
 #pragma unroll
       for (int t8 = 0; t8 < 2; ++t8) {
         const int qq = mt * 32 + 16 * t8 + 8 * hl;
@@ -346,6 +353,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
             dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - dv[e]), p1 * (pacc[i + 1] - dv[e + 1]));
         }
       }
+      __builtin_amdgcn_s_setprio(0);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         const uint32_t *w = DO_DV ? pb : dsb;
