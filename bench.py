@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the forward kernel at the default workload (wan, density 0.25, seed 42,
+# with the O residual written): rocprofv3 FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors read
+# off the transposition kernel of the same run (profiles/wan_b128_d128_density25_step_hbm_traffic.md)
+FWD_TRAFFIC_BYTES_WAN25 = 1163832 * 1024 * 2.00 + 259548 * 1024 * 1.00
 
 
 def parse():
@@ -172,7 +176,7 @@ def main():
                                             "min": round(float(bwd_ms.min()), 4)},
         "bwd_tflops": None if args.no_bwd else round(float(bwd_tflops), 2),
         "roofline": {
-            "kernel": f"fwd_kernel<{p.block},{p.d}>",
+            "kernel": f"fwd_pp_kernel<{p.block},{p.d}>",
             "bound": "mfma",
             "achieved": round(float(kern_tflops), 2),
             "peak": PEAK_BF16_TFLOPS,
@@ -180,7 +184,9 @@ def main():
             "frac": round(float(kern_tflops / PEAK_BF16_TFLOPS), 4),
             "kernel_ms": round(float(kern_ms.mean()), 4),
             "flops_per_launch": fwd_flops,
-            "traffic": None,
+            "traffic": (round(FWD_TRAFFIC_BYTES_WAN25) if (args.workload == "wan" and abs(dens - 0.25) < 1e-9
+                                                           and args.seed == 42 and not args.no_bwd) else None),
+            "traffic_unit": "HBM bytes per launch, from the committed rocprofv3 counter summary",
         },
         "paper_context": "BLADE reports 22.21 ms ASA vs 73.25 ms dense FA2 on one H20 at this shape "
                          "(sparsity 0.798) and 14.10x / 8.89x end-to-end speedups; other hardware, "
