@@ -288,9 +288,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
 //    instructions completely.  With the VECTOR wavefront at the higher priority both run: the
 //    MFMA stream loses nothing and the vector stream runs at ~80 % of its stand-alone rate.
 //  * One 64 x 16 B direct-to-LDS load occupies the issuing wavefront for 65..90 cycles (much
-//    more on a wavefront of lower priority).  The copies are therefore requested by the
-//    vector group (it has the priority and no MFMA stream to hold up), a few at a time between
-//    blocks of soft-max arithmetic.
+//    more on a low-priority wavefront that competes with a busy one).  The copies of a phase
+//    are requested by its vector group (it has the priority and no MFMA stream to hold up), one
+//    at a time between blocks of soft-max arithmetic.  Never as a burst behind the barrier.
 //  * Scalar bookkeeping shows up directly as idle matrix time (the scalar unit is shared):
 //    the phase loop is unrolled so that p mod 4 is a compile-time constant, every LDS address
 //    is an immediate, and the column list is turned once into byte offsets of the K and V^T
@@ -369,12 +369,15 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale_log2e;
 
-  // The copies of a phase are requested by its VECTOR group (wavefront wq copies a quarter
-  // -- BLK = 64: half -- of each tile).
+  // Copies: wavefront wq of the requesting group copies a quarter (BLK = 64: half) of a tile.
   RowTileCopy<C::kKT, D, C::kGroupWaves> copy_k;
   ColTileCopy<BLK, D, C::kGroupWaves> copy_v;
   copy_k.init(wq, lane, a.tk.sL);
   copy_v.init(wq, lane);
+  // false: all copies of a phase by its vector group; true: K copies by the matrix group after
+  // its last MFMA, V copies by the vector group.  Within 2 % of each other (true is ahead on
+  // iid inputs, false on the video-like inputs of the benchmark).
+  constexpr bool kSplitCopies = false;
   constexpr int kInstrK = RowTileCopy<C::kKT, D, C::kGroupWaves>::kInstr;
   constexpr int kBatchInstr = kInstrK + ColTileCopy<BLK, D, C::kGroupWaves>::kInstr;
   static_assert(kBatchInstr == 4 || kBatchInstr == 8 || kBatchInstr == 16, "unexpected copy size");
@@ -429,11 +432,11 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
 #pragma unroll
   for (int e = 0; e < (C::kKT / 32) * 8; ++e) pb[e] = 0;
 
-  // Start of phase p (R = p mod 4).  The vector group of phase p requests, spread over that
-  // phase, K of step p+3 and V of step p+1 (their buffers were last read in phase p-1).  Data
-  // needed in phase p -- K(p), V(p-2) -- was requested during phase p-3 by the group that has
-  // just finished phase p-1's vector work: "all of my copies but the newest batch have landed"
-  // on every wavefront, followed by the barrier, makes it visible to all.
+  // Start of phase p (R = p mod 4).  During phase p, K of step p+3 and V of step p+1 are
+  // requested (their buffers were last read in phase p-1); every wavefront requests the same
+  // number of loads per two phases.  Data needed in phase p -- K(p), V(p-2) -- was requested
+  // during phase p-3: "all of my copies but the newest kBatchInstr have landed" on every
+  // wavefront, followed by the barrier, makes it visible to all.
   auto phase_sync = [&](int p) __attribute__((always_inline)) {
     __builtin_amdgcn_sched_barrier(0);
     if (kBatchInstr == 4) __builtin_amdgcn_s_waitcnt(0x0F74);
@@ -481,11 +484,19 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     else
       copy_v.issue_one_at(i - kInstrK, ldsV_addr + ((R + 1) & 3) * C::kVElems * 2, v_base[sb] + ev_cur);
   };
-  auto dma_all = [&](auto r_tag) __attribute__((always_inline)) {
-    dma_prepare(r_tag);
-    __builtin_amdgcn_sched_barrier(0);
+  // (idle phases) matrix_slot: this group is the phase's matrix group
+  auto dma_idle = [&](auto r_tag, bool matrix_slot) __attribute__((always_inline)) {
+    if (kSplitCopies ? matrix_slot : false) {
+      dma_prepare(r_tag);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
+      for (int i = 0; i < kInstrK; ++i) dma_one(r_tag, i);
+    } else if (!matrix_slot) {
+      if (!kSplitCopies) dma_prepare(r_tag);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = kSplitCopies ? kInstrK : 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
   // MATRIX phase p (R = p mod 4): P V of step p-2 followed by S^T of step p.  One wavefront
@@ -530,6 +541,14 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_setprio(3);
+    if (kSplitCopies) {
+      // all MFMAs of the phase are issued: request this wavefront's K copies while they drain
+      dma_prepare(r_tag);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < kInstrK; ++i) dma_one(r_tag, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
   // VECTOR phase p: online soft-max of step p-1 (RX = that step mod 4), whose S^T is in sacc;
@@ -539,7 +558,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     constexpr int sb = decltype(rx_tag)::value % C::kSub;
     const Int<(decltype(rx_tag)::value + 1) & 3> r_tag{};   // the phase this runs in
     constexpr int kPortion = kBatchInstr / 8 > 0 ? kBatchInstr / 8 : 1;
-    int next_copy = 0;
+    int next_copy = kSplitCopies ? kInstrK : 0;
     auto request = [&](int n_instr) __attribute__((always_inline)) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -548,7 +567,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     };
     __builtin_amdgcn_s_setprio(3);
-    dma_prepare(r_tag);
+    if (!kSplitCopies) dma_prepare(r_tag);
     if (ev_older == v_tail[sb]) {
       const int key0 = last_row0 + sb * C::kKT;
 #pragma unroll
@@ -604,7 +623,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     using R2 = Int<(G + 2) & 3>;
     using R3 = Int<(G + 3) & 3>;
     int p = 0;
-    if (G == 1) { phase_sync(p); dma_all(Int<0>{}); ++p; }   // group 0's matrix slot, my copies
+    if (G == 1) { phase_sync(p); dma_idle(Int<0>{}, false); ++p; }   // group 0's matrix slot
     const int n_own = n_steps > G ? (n_steps - G + 1) / 2 : 0;
     if (n_own > 0) {
       phase_sync(p); do_matrix(R0{}, no, yes); ++p;
@@ -627,10 +646,10 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     // the other group may still have phases to run: keep the barriers and copies in step
     for (; p < n_steps + 2; ++p) {
       switch (p & 3) {
-        case 0: phase_sync(p); if (G == 1) dma_all(Int<0>{}); break;
-        case 1: phase_sync(p); if (G == 0) dma_all(Int<1>{}); break;
-        case 2: phase_sync(p); if (G == 1) dma_all(Int<2>{}); break;
-        default: phase_sync(p); if (G == 0) dma_all(Int<3>{}); break;
+        case 0: phase_sync(p); dma_idle(Int<0>{}, G == 0); break;
+        case 1: phase_sync(p); dma_idle(Int<1>{}, G == 1); break;
+        case 2: phase_sync(p); dma_idle(Int<2>{}, G == 0); break;
+        default: phase_sync(p); dma_idle(Int<3>{}, G == 1); break;
       }
     }
   };
