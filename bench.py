@@ -2,14 +2,16 @@
 """Benchmark of the ASA hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan|cog|wan-padded]
-                    [--density 0.25] [--no-bwd] [--no-cpu-baseline]
+                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref]
 
 One step = one pass of the whole path over one batch of seeded synthetic video-token tensors
 that are already resident in HBM: mask generation (asa_build_mask), block-sparse forward
 (asa_attn_fwd) and backward (asa_attn_bwd).  The reported value is the forward's effective
 throughput on executed tiles, 4*b*b*d FLOP per kept (query block, key block) pair divided by
 the forward call's time (the call includes the V transposition it needs); mask and backward
-times are reported beside it.  Prints ONE JSON line.
+times are reported beside it, and so is the same forward call run dense (no index lists) with the
+ratio dense / (mask + sparse forward), the in-house counterpart of the paper's kernel speedup
+(Table 2).  Prints ONE JSON line.
 """
 
 from __future__ import annotations
@@ -46,6 +48,7 @@ def parse():
     ap.add_argument("--seed", type=int, default=42)
     ap.add_argument("--no-bwd", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-ref", action="store_true")
     ap.add_argument("--cpu-sample-slabs", type=int, default=3)
     return ap.parse_args()
 
@@ -127,6 +130,18 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3
 
+    # in-house dense baseline of the kernel-speedup ratio: the same forward call without index
+    # lists (every key block), a few repetitions outside the timed steps
+    dense_ms = None
+    if not args.no_dense_ref:
+        d_ev = [(ev(), ev()) for _ in range(4)]
+        for a_ev, b_ev in d_ev:
+            a_ev.record(stream)
+            binding.asa_attn_fwd(p, q, k, v, None, None, o, lse, ws_fwd, o_lo=None)
+            b_ev.record(stream)
+        torch.cuda.synchronize()
+        dense_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[1:]]))
+
     mask_ms = np.array([e["s0"].elapsed_time(e["s1"]) for e in per_step])
     fwd_ms = np.array([e["s1"].elapsed_time(e["s2"]) for e in per_step])
     bwd_ms = np.array([e["s2"].elapsed_time(e["s3"]) for e in per_step])
@@ -175,6 +190,11 @@ def main():
         "bwd_ms": None if args.no_bwd else {"median": round(float(np.median(bwd_ms)), 4),
                                             "min": round(float(bwd_ms.min()), 4)},
         "bwd_tflops": None if args.no_bwd else round(float(bwd_tflops), 2),
+        "dense_fwd_ms": None if dense_ms is None else round(dense_ms, 4),
+        "dense_fwd_tflops": None if dense_ms is None else round(
+            p.B * p.H * p.Nb * p.Nb * tile_flops / (dense_ms * 1e-3) / 1e12, 2),
+        "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
+            dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
         "roofline": {
             "kernel": f"fwd_pp_kernel<{p.block},{p.d}>",
             "bound": "mfma",

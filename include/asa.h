@@ -123,6 +123,10 @@ int asa_csr_from_mask(const asa_params *p, const uint8_t *mask, int32_t *row_ptr
  *      more than the 8 significant bits of o there.
  * lse  [B*H, L] fp32, natural logarithm; a row with an empty list gets O = 0, LSE = -inf
  * bf16 products accumulate in fp32; probabilities are rounded to bf16 before P V.
+ * row_ptr = col_idx = NULL selects the dense specialisation (every key block, no index
+ * lists read): the dense attention of the first two sampling steps (Sec. 4.3) and the
+ * in-house dense baseline of the kernel-speedup ratio (Table 2); exactly one of them NULL is
+ * ASA_ERR_INVALID_ARG.
  */
 int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *v,
                  const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo, float *lse,
@@ -136,6 +140,8 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
  * o, o_lo, lse are the forward's outputs (o_lo may be NULL: Delta then comes from the bf16 o
  * alone); col_ptr/row_idx is the mask by columns.
  * dq, dk, dv [B, H, L, d] bf16 (q/k/v strides); every row < L is written.
+ * All four index-list pointers NULL selects the dense specialisation (see asa_attn_fwd);
+ * some but not all NULL is ASA_ERR_INVALID_ARG.
  */
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
                  const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,

@@ -200,7 +200,8 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
   Problem pb;
   int rc = resolve(p, &pb);
   if (rc != ASA_OK) return rc;
-  if (!q || !k || !v || !row_ptr || !col_idx || !o || !lse) return ASA_ERR_INVALID_ARG;
+  if (!q || !k || !v || !o || !lse) return ASA_ERR_INVALID_ARG;
+  if ((row_ptr == nullptr) != (col_idx == nullptr)) return ASA_ERR_INVALID_ARG;   // both or neither (dense)
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||
       !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx))
     return ASA_ERR_INVALID_ARG;
@@ -222,7 +223,11 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
   Problem pb;
   int rc = resolve(p, &pb);
   if (rc != ASA_OK) return rc;
-  if (!q || !k || !v || !o || !d_o || !lse || !row_ptr || !col_idx || !col_ptr || !row_idx ||
+  {
+    const int n_lists = (row_ptr != nullptr) + (col_idx != nullptr) + (col_ptr != nullptr) + (row_idx != nullptr);
+    if (n_lists != 0 && n_lists != 4) return ASA_ERR_INVALID_ARG;   // all four or none (dense)
+  }
+  if (!q || !k || !v || !o || !d_o || !lse ||
       !dq || !dk || !dv)
     return ASA_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||

@@ -111,11 +111,12 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   const bf16 *vs = slab_ptr(a.v, a.tv, slab, a.H);
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
   const bf16 *kts = a.kt + (int64_t)slab * D * a.Lpad;
-  const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  const bool dense = a.row_ptr == nullptr;   // no index lists: every key block
+  const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
+  const int n_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
   {
     const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = g[t];
+    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = dense ? t : g[t];
   }
 
   const int qrow = qb * BLK + wave * 32 + n;
@@ -255,11 +256,12 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
   const bf16 *qts = a.qt + (int64_t)slab * D * a.Lpad;
   const bf16 *gts = a.dot + (int64_t)slab * D * a.Lpad;
-  const int t_begin = a.col_ptr[slab * (a.Nb + 1) + kb];
-  const int n_tiles = a.col_ptr[slab * (a.Nb + 1) + kb + 1] - t_begin;
+  const bool dense = a.col_ptr == nullptr;   // no index lists: every query block
+  const int t_begin = dense ? 0 : a.col_ptr[slab * (a.Nb + 1) + kb];
+  const int n_tiles = dense ? a.Nb : a.col_ptr[slab * (a.Nb + 1) + kb + 1] - t_begin;
   {
     const int32_t *g = a.row_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) rows[t] = g[t];
+    for (int t = tid; t < n_tiles; t += C::kThreads) rows[t] = dense ? t : g[t];
   }
 
   const int krow = kb * BLK + wave * 32 + n;

@@ -124,11 +124,13 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vts = a.vt + (int64_t)slab * D * a.Lpad;
-  const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  // no index lists: dense attention, every key block in order
+  const bool dense = a.row_ptr == nullptr;
+  const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
+  const int n_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
   {
     const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = g[t];
+    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = dense ? t : g[t];
   }
   const int qrow = qb * BLK + wave * 32 + n;
   const bool qvalid = qrow < a.L;
@@ -339,8 +341,10 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vts = a.vt + (int64_t)slab * D * a.Lpad;
-  const int t_begin = a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int n_tiles = a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  // no index lists: dense attention, every key block in order
+  const bool dense = a.row_ptr == nullptr;
+  const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
+  const int n_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
   const int n_steps = n_tiles * C::kSub;
   const uint32_t pitch_bytes = (uint32_t)a.tk.sL * 2u;
   const uint32_t k_tile_bytes = BLK * pitch_bytes;     // host checked: Nb * this < 2^32
@@ -349,7 +353,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
     for (int t = tid; t < n_tiles + C::kTabPad; t += C::kThreads) {
       const int tc = t < n_tiles ? t : n_tiles - 1;
-      const uint32_t j = n_tiles > 0 ? (uint32_t)g[tc] : 0u;
+      const uint32_t j = n_tiles > 0 ? (dense ? (uint32_t)tc : (uint32_t)g[tc]) : 0u;
       tabK[t] = j * k_tile_bytes;
       tabV[t] = j * v_tile_bytes;
     }

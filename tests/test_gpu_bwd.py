@@ -55,6 +55,30 @@ def test_bwd_random_masks(B, H, L, d, block, dens):
     _check_bwd(p, qb, kb, vb, gb, mask, with_lo=False)
 
 
+@pytest.mark.parametrize("L,d,block", [(640, 128, 128), (333, 64, 64)])
+def test_bwd_dense_specialisation_needs_no_lists(L, d, block):
+    """All four list pointers NULL: the same tiles in the same order as a full mask's lists,
+    hence bit-identical gradients (the full-mask path is checked against the oracle above)."""
+    print(f"case dense L={L} d={d} block={block}", flush=True)
+    p = binding.Params(B=1, H=2, L=L, d=d, block=block)
+    shape = (1, 2, L, d)
+    qb, kb, vb, gb = (synth.make_iid(shape, L + d, s) for s in range(4))
+    q, k, v, g = (util.dev_bf16(x) for x in (qb, kb, vb, gb))
+    mask = np.ones((2, p.Nb, p.Nb), np.uint8)
+    full = util.lists_from_mask(p, mask)
+    none = {"row_ptr": None, "col_idx": None, "col_ptr": None, "row_idx": None}
+    o, lse, o_lo = util.run_fwd(p, q, k, v, none, with_lo=True)
+    want = util.run_bwd(p, q, k, v, o, lse, g, full, o_lo=o_lo)
+    got = util.run_bwd(p, q, k, v, o, lse, g, none, o_lo=o_lo)
+    for a, b, name in zip(got, want, ("dQ", "dK", "dV")):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), name
+    qf, kf, vf, gf = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb, gb))
+    wq, wk, wv = oracle.attn_bwd(qf[0, 1], kf[0, 1], vf[0, 1], gf[0, 1], mask[1], block, None)
+    util.assert_close_bf16(util.host_f32(got[0])[0, 1], wq, "dense dQ")
+    util.assert_close_bf16(util.host_f32(got[1])[0, 1], wk, "dense dK")
+    util.assert_close_bf16(util.host_f32(got[2])[0, 1], wv, "dense dV")
+
+
 def test_bwd_empty_rows_and_columns():
     p = binding.Params(B=1, H=1, L=384, d=64, block=64)
     shape = (1, 1, 384, 64)

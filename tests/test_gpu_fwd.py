@@ -66,6 +66,36 @@ def test_fwd_all_blocks_kept_is_dense_attention():
     util.assert_close_bf16(util.host_f32(o), want, "dense O")
 
 
+@pytest.mark.parametrize("L,d,block", [(640, 128, 128), (1000, 64, 64), (333, 128, 64)])
+def test_fwd_dense_specialisation_needs_no_lists(L, d, block):
+    """row_ptr = col_idx = NULL: every key block.  Same tiles in the same order as a full mask's
+    lists, so bit-identical to that call; and equal to plain soft-max attention."""
+    print(f"case dense L={L} d={d} block={block}", flush=True)
+    p = binding.Params(B=1, H=2, L=L, d=d, block=block)
+    qb, kb, vb = _case(1, 2, L, d, block, seed=11)
+    q, k, v = (util.dev_bf16(x) for x in (qb, kb, vb))
+    full = util.lists_from_mask(p, np.ones((2, p.Nb, p.Nb), np.uint8), with_csc=False)
+    o_ref, lse_ref = util.run_fwd(p, q, k, v, full)
+    o, lse = util.run_fwd(p, q, k, v, {"row_ptr": None, "col_idx": None})
+    assert torch.equal(o.view(torch.int16), o_ref.view(torch.int16))
+    assert torch.equal(lse, lse_ref)
+    qf, kf, vf = (torch.from_numpy(synth.bf16_bits_to_f32(x).astype(np.float64)) for x in (qb, kb, vb))
+    want = torch.nn.functional.scaled_dot_product_attention(qf, kf, vf).numpy()
+    util.assert_close_bf16(util.host_f32(o), want, "dense O")
+
+
+def test_fwd_single_stage_kernel_is_still_correct(monkeypatch):
+    """The kernel that takes over for slabs of 4 GiB and more, forced by its switch."""
+    monkeypatch.setenv("ASA_FWD_PLAIN", "1")
+    p = binding.Params(B=1, H=2, L=1000, d=128, block=128)
+    qb, kb, vb = _case(1, 2, 1000, 128, 128, seed=5)
+    mask = synth.random_block_mask(p.Nb, 0.5, seed=5, slabs=2)
+    _check_fwd(p, qb, kb, vb, mask)
+    p = binding.Params(B=1, H=1, L=520, d=64, block=64)
+    qb, kb, vb = _case(1, 1, 520, 64, 64, seed=6)
+    _check_fwd(p, qb, kb, vb, synth.random_block_mask(p.Nb, 0.6, seed=6, slabs=1))
+
+
 def test_fwd_tiny_workload_with_oracle_mask():
     w = synth.TINY
     qb, kb, vb = synth.make_qkv(w, seed=0)

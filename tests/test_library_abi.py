@@ -50,6 +50,15 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert L.asa_build_mask(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1
     assert L.asa_mask_from_scores(ctypes.byref(p.c()), None, None, None) == -1
     assert L.asa_bwd_workspace_bytes(ctypes.byref(p.c())) == 3 * 2 * 64 * 1024 * 2 + 2 * 1024 * 4
+    # index lists: both (forward) / all four (backward) or none (dense); anything else is refused
+    # before the pointers are looked at (the addresses below are never dereferenced)
+    fake = ctypes.c_void_p(0x10000)
+    assert L.asa_attn_fwd(ctypes.byref(p.c()), fake, fake, fake, fake, None, fake, None, fake,
+                          fake, 1 << 30, None) == -1
+    assert L.asa_attn_fwd(ctypes.byref(p.c()), fake, fake, fake, None, fake, fake, None, fake,
+                          fake, 1 << 30, None) == -1
+    assert L.asa_attn_bwd(ctypes.byref(p.c()), fake, fake, fake, fake, None, fake, fake,
+                          fake, fake, fake, None, fake, fake, fake, fake, 1 << 30, None) == -1
     for bad in (dict(k_samples=0), dict(k_samples=65), dict(sample_offsets=[3, 1] + list(range(4, 18))),
                 dict(r_min=0.6, r_max=0.5), dict(tau=float("nan")), dict(n_prefix_dense=-1),
                 dict(q_stride=(0, 0, 60))):
