@@ -149,6 +149,36 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
                  void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ASA with global tokens, ASA_G (Sec. 3.3, "ASA with Global Tokens"): K and V are extended by
+ * mean-pooled copies of themselves, K_aug = Concat(K, MeanPool_n(K)) and likewise V.  A query
+ * sees the original keys through the block mask exactly as in asa_attn_fwd and, in addition,
+ * EVERY pooled key, with ln(n) added to its pre-soft-max score.
+ *
+ * The pooled part is kept in tensors of its own:
+ *   kg, vg [B, H, G, d] bf16, contiguous, G = asa_global_token_count(p, n) = ceil(L/n) rounded
+ *   up to a multiple of `block`.  Row w < ceil(L/n) is the mean of tokens [w n, min(L, (w+1) n))
+ *   formed in fp32 and rounded to bf16 (the tensor type); rows past ceil(L/n) are zero and are
+ *   never attended.  The bias is ln(n) for every window, the short last one included.
+ * asa_global_tokens writes kg and vg from k and v.  n: 1 <= n <= L; ceil(L/block) +
+ * G/block may not exceed 1024 (ASA_ERR_UNSUPPORTED).
+ */
+size_t asa_global_token_count(const asa_params *p, int n);   /* 0 on invalid arguments */
+int asa_global_tokens(const asa_params *p, int n, const void *k, const void *v, void *kg,
+                      void *vg, void *hip_stream);
+
+/*
+ * Forward of ASA_G: as asa_attn_fwd with the pooled keys / values kg, vg of window n appended
+ * (NULL index lists: dense over the original keys, plus the pooled ones).  LSE covers both
+ * parts.  Workspace: asa_fwd_g_workspace_bytes.  Tensors whose (batch, head) slab of K spans
+ * 4 GiB or more are ASA_ERR_UNSUPPORTED here.
+ */
+size_t asa_fwd_g_workspace_bytes(const asa_params *p, int n);
+int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,
+                   const void *kg, const void *vg, const int32_t *row_ptr, const int32_t *col_idx,
+                   void *o, void *o_lo, float *lse, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
+
+/*
  * Profiling hook for benchmarks.  Arms the calling thread so that the NEXT asa_attn_fwd,
  * asa_attn_bwd or asa_build_mask call records `start_event` immediately before and
  * `stop_event` immediately after its dominant kernel(s) -- the tile loop of the forward, the

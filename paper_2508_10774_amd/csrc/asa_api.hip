@@ -216,6 +216,96 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
   return finish(e);
 }
 
+// ------------------------------------------------------------------ ASA_G (global tokens)
+static int global_dims(const Problem &pb, int n, int *Lg, int *Nbg) {
+  if (n < 1 || n > pb.L) return ASA_ERR_INVALID_ARG;
+  *Lg = (pb.L + n - 1) / n;
+  *Nbg = (*Lg + pb.block - 1) / pb.block;
+  if (pb.Nb + *Nbg > kMaxNb) return ASA_ERR_UNSUPPORTED;
+  return ASA_OK;
+}
+static size_t pooled_tile_bytes(const Problem &pb, int Nbg) {
+  return round256((size_t)pb.n_slabs * Nbg * pb.block * pb.d * sizeof(uint16_t));
+}
+// the pooled tensors seen as a problem of their own (contiguous [B, H, Nbg * block, d])
+static Problem pooled_problem(const Problem &pb, int Lg, int Nbg) {
+  Problem g = pb;
+  g.L = Lg;
+  g.Nb = Nbg;
+  g.Lpad = Nbg * pb.block;
+  TensorView tv;
+  tv.sL = pb.d;
+  tv.sH = (int64_t)g.Lpad * pb.d;
+  tv.sB = tv.sH * pb.H;
+  g.q = g.k = g.v = g.o = tv;
+  return g;
+}
+
+size_t asa_global_token_count(const asa_params *p, int n) {
+  Problem pb;
+  int Lg, Nbg;
+  if (resolve(p, &pb) != ASA_OK || global_dims(pb, n, &Lg, &Nbg) != ASA_OK) return 0;
+  return (size_t)Nbg * pb.block;
+}
+
+int asa_global_tokens(const asa_params *p, int n, const void *k, const void *v, void *kg, void *vg,
+                      void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  int Lg, Nbg;
+  rc = global_dims(pb, n, &Lg, &Nbg);
+  if (rc != ASA_OK) return rc;
+  if (!k || !v || !kg || !vg) return ASA_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(kg) || !aligned16(vg)) return ASA_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = launch_pool(pb, n, k, pb.k, kg, st);
+  if (e != hipSuccess) return finish(e);
+  return finish(launch_pool(pb, n, v, pb.v, vg, st));
+}
+
+size_t asa_fwd_g_workspace_bytes(const asa_params *p, int n) {
+  Problem pb;
+  int Lg, Nbg;
+  if (resolve(p, &pb) != ASA_OK || global_dims(pb, n, &Lg, &Nbg) != ASA_OK) return 0;
+  return transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg);
+}
+
+int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,
+                   const void *kg, const void *vg, const int32_t *row_ptr, const int32_t *col_idx,
+                   void *o, void *o_lo, float *lse, void *workspace, size_t workspace_bytes,
+                   void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  int Lg, Nbg;
+  rc = global_dims(pb, n, &Lg, &Nbg);
+  if (rc != ASA_OK) return rc;
+  if (!q || !k || !v || !kg || !vg || !o || !lse) return ASA_ERR_INVALID_ARG;
+  if ((row_ptr == nullptr) != (col_idx == nullptr)) return ASA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(kg) || !aligned16(vg) ||
+      !aligned16(o) || !aligned16(o_lo) || !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx))
+    return ASA_ERR_INVALID_ARG;
+  if ((uint64_t)pb.Nb * pb.block * (uint64_t)pb.k.sL * 2u >= 0xFFFFFFFFull) return ASA_ERR_UNSUPPORTED;
+  if (!workspace || workspace_bytes < transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg) ||
+      !aligned16(workspace))
+    return ASA_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char *ws = reinterpret_cast<char *>(workspace);
+  void *vgt = ws + transposed_bytes(pb);
+  hipError_t e = launch_transpose(pb, v, pb.v, ws, st);
+  if (e != hipSuccess) return finish(e);
+  const Problem g = pooled_problem(pb, Lg, Nbg);
+  e = launch_transpose(g, vg, g.v, vgt, st);
+  if (e != hipSuccess) return finish(e);
+  GlobalTokens gt;
+  gt.n = n; gt.Lg = Lg; gt.Nbg = Nbg; gt.kg = kg; gt.vg = vg; gt.vgt = vgt;
+  timing_begin(st);
+  e = launch_fwd(pb, q, k, ws, row_ptr, col_idx, o, o_lo, lse, st, &gt);
+  timing_end(st);
+  return finish(e);
+}
+
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
                  const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,

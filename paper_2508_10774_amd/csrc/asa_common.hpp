@@ -53,9 +53,19 @@ void timing_end(hipStream_t st);
 // launchers (each returns a hipError_t from the launch)
 hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView &tv, void *dst,
                             hipStream_t st);
+// Global tokens of ASA_G as the attention kernels see them (all device pointers).
+struct GlobalTokens {
+  int n;              // pooling window
+  int Lg, Nbg;        // pooled tokens per slab; key blocks they fill (rows padded to Nbg * block)
+  const void *kg;     // [slab][Nbg * block][d] bf16
+  const void *vg;     // [slab][Nbg * block][d] bf16
+  const void *vgt;    // [slab][Nbg][d][block] bf16, transposed tiles of vg (workspace)
+};
+hipError_t launch_pool(const Problem &pb, int n, const void *src, const TensorView &tv, void *dst,
+                       hipStream_t st);
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
                       const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
-                      float *lse, hipStream_t st);
+                      float *lse, hipStream_t st, const GlobalTokens *gt = nullptr);
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,

@@ -73,6 +73,35 @@ hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView
 }
 
 // ---------------------------------------------------------------------------------------
+// Global tokens of ASA_G (Sec. 3.3): MeanPool_n over the token axis.  One workgroup per pooled
+// row, one thread per channel; the mean of the window's valid tokens is formed in fp32 and
+// rounded to bf16 (the tensor type of K_aug / V_aug); rows past Lg are zero.
+// ---------------------------------------------------------------------------------------
+__global__ void pool_kernel(const void *src, TensorView tv, int H, int L, int d, int n, int Lg,
+                            int Lg_pad, bf16 *dst) {
+  const int w = blockIdx.x, slab = blockIdx.y, c = threadIdx.x;
+  bf16 *out = dst + ((int64_t)slab * Lg_pad + w) * d;
+  if (w >= Lg) {
+    out[c] = (bf16)0.f;
+    return;
+  }
+  const bf16 *x = slab_ptr(src, tv, slab, H);
+  const int r0 = w * n, r1 = min(L, r0 + n);
+  float acc = 0.f;
+  for (int r = r0; r < r1; ++r) acc += (float)x[(int64_t)r * tv.sL + c];
+  out[c] = (bf16)(acc / (float)(r1 - r0));
+}
+
+hipError_t launch_pool(const Problem &pb, int n, const void *src, const TensorView &tv, void *dst,
+                       hipStream_t st) {
+  const int Lg = (pb.L + n - 1) / n;
+  const int Lg_pad = ((Lg + pb.block - 1) / pb.block) * pb.block;
+  hipLaunchKernelGGL(pool_kernel, dim3(Lg_pad, pb.n_slabs), dim3(pb.d), 0, st, src, tv, pb.H, pb.L,
+                     pb.d, n, Lg, Lg_pad, reinterpret_cast<bf16 *>(dst));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // forward kernel
 // ---------------------------------------------------------------------------------------
 struct FwdArgs {
@@ -84,6 +113,11 @@ struct FwdArgs {
   TensorView tq, tk, to;
   int H, L, Lpad, Nb, n_slabs;
   float scale_log2e;  // scale * log2(e)
+  // global tokens (ASA_G); Nbg = 0 switches them off
+  const void *kg;     // [slab][Nbg * block][d] bf16 pooled keys, zero rows past Lg
+  const bf16 *vgt;    // [slab][Nbg][d][block]: pooled values, transposed tiles
+  int Lg, Nbg;        // pooled tokens per slab, key blocks they fill
+  float bias_log2;    // log2(n): the additive ln(n) of the pooled scores, in the exp2 domain
 };
 
 template <int BLK, int D>
@@ -318,7 +352,8 @@ struct PpCfg {
 template <int N>
 using Int = std::integral_constant<int, N>;
 
-template <int BLK, int D>
+// GT: with the pooled (global) tokens of ASA_G appended to every query block's list
+template <int BLK, int D, bool GT>
 __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   using C = PpCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
@@ -344,8 +379,11 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   // no index lists: dense attention, every key block in order
   const bool dense = a.row_ptr == nullptr;
   const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int n_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  const int n_own_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  // global tokens: Nbg more key blocks that every query block visits, after its own list
+  const int n_tiles = n_own_tiles + (GT ? a.Nbg : 0);
   const int n_steps = n_tiles * C::kSub;
+  const int n_own_steps = n_own_tiles * C::kSub;
   const uint32_t pitch_bytes = (uint32_t)a.tk.sL * 2u;
   const uint32_t k_tile_bytes = BLK * pitch_bytes;     // host checked: Nb * this < 2^32
   constexpr uint32_t v_tile_bytes = D * BLK * 2;
@@ -353,9 +391,17 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
     for (int t = tid; t < n_tiles + C::kTabPad; t += C::kThreads) {
       const int tc = t < n_tiles ? t : n_tiles - 1;
-      const uint32_t j = n_tiles > 0 ? (dense ? (uint32_t)tc : (uint32_t)g[tc]) : 0u;
-      tabK[t] = j * k_tile_bytes;
-      tabV[t] = j * v_tile_bytes;
+      if (tc < n_own_tiles) {
+        const uint32_t j = dense ? (uint32_t)tc : (uint32_t)g[tc];
+        tabK[t] = j * k_tile_bytes;
+        tabV[t] = j * v_tile_bytes;
+      } else if (n_tiles > 0) {   // pooled tile tc - n_own_tiles, rows of D elements
+        tabK[t] = (uint32_t)(tc - n_own_tiles) * (BLK * D * 2);
+        tabV[t] = (uint32_t)(tc - n_own_tiles) * v_tile_bytes;
+      } else {
+        tabK[t] = 0;
+        tabV[t] = 0;
+      }
     }
   }
   const int qrow = qb * BLK + wq * 32 + n;
@@ -404,6 +450,13 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     k_base[sb] = reinterpret_cast<const char *>(ks) + (int64_t)sb * C::kKT * pitch_bytes;
     v_base[sb] = reinterpret_cast<const char *>(vts) + sb * C::kKT * 2;
   }
+  // pooled keys / values of this slab (rows of D elements; tiles like V's)
+  const char *kg_slab = reinterpret_cast<const char *>(a.kg) + (int64_t)slab * a.Nbg * BLK * D * 2;
+  const char *vg_slab = reinterpret_cast<const char *>(a.vgt) + (int64_t)slab * a.Nbg * D * BLK * 2;
+  // is step s one over pooled tokens?  (steps past the end repeat the last step)
+  auto pooled_step = [&](int step) __attribute__((always_inline)) {
+    return GT && (step < n_steps ? step : n_steps - 1) >= n_own_steps;
+  };
 
   __syncthreads();   // tables complete
   // Before phase 0: K of steps 0, 1, 2 and V of step 0 (group 0: K(0), K(2); group 1: K(1),
@@ -413,14 +466,22 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     auto k_step = [&](int step) __attribute__((always_inline)) {
       const int j = (int)(__builtin_amdgcn_readfirstlane(tabV[step / C::kSub]) / v_tile_bytes);
       const int r = j * BLK + (step % C::kSub) * C::kKT;
-      copy_k.issue_at_ragged(ldsK_addr + step * C::kKElems * 2, kb + (int64_t)r * pitch_bytes, a.L - 1 - r);
+      if (pooled_step(step)) {
+#pragma unroll
+        for (int i = 0; i < kInstrK; ++i)
+          lds_dma16_sv(kg_slab + (int64_t)r * (D * 2),
+                       copy_k.off[i] - (uint32_t)copy_k.row_of(i) * (pitch_bytes - D * 2),
+                       ldsK_addr + step * C::kKElems * 2 + copy_k.lds_chunk(i));
+      } else {
+        copy_k.issue_at_ragged(ldsK_addr + step * C::kKElems * 2, kb + (int64_t)r * pitch_bytes, a.L - 1 - r);
+      }
     };
     if (grp == 0) {
       k_step(0);
       k_step(2);
     } else {
       k_step(1);
-      copy_v.issue_at(ldsV_addr, v_base[0] + __builtin_amdgcn_readfirstlane(tabV[0]));
+      copy_v.issue_at(ldsV_addr, (pooled_step(0) ? vg_slab : v_base[0]) + __builtin_amdgcn_readfirstlane(tabV[0]));
     }
   }
   // Table entries of the copies of phase 0 (K of step 3, V of step 1) and the V entries of the
@@ -441,6 +502,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   // number of loads per two phases.  Data needed in phase p -- K(p), V(p-2) -- was requested
   // during phase p-3: "all of my copies but the newest kBatchInstr have landed" on every
   // wavefront, followed by the barrier, makes it visible to all.
+  int phase_now = 0;   // the phase in progress, set by phase_sync
   auto phase_sync = [&](int p) __attribute__((always_inline)) {
     __builtin_amdgcn_sched_barrier(0);
     if (kBatchInstr == 4) __builtin_amdgcn_s_waitcnt(0x0F74);
@@ -448,6 +510,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     else __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): low bits 0, high bits (15:14) 1
     asm volatile("s_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
+    phase_now = p;
     ek_cur = __builtin_amdgcn_readfirstlane(ek_next);
     ev_older = ev_last;
     ev_last = ev_cur;
@@ -459,13 +522,24 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
 
   // The K copy of this phase: wave-uniform base and per-lane offsets.  Normally the offsets are
   // the tile's own; for the one ragged step they are bent back to the last row (rare branch).
-  const char *kdma_base = nullptr;
+  const char *kdma_base = nullptr, *vdma_base = nullptr;
   uint32_t kdma_off[kInstrK];
   auto dma_prepare = [&](auto r_tag) __attribute__((always_inline)) {
     constexpr int sb = (decltype(r_tag)::value + 1) % C::kSub;
     kdma_base = k_base[sb] + ek_cur;
+    vdma_base = v_base[sb] + ev_cur;
 #pragma unroll
     for (int i = 0; i < kInstrK; ++i) kdma_off[i] = copy_k.off[i];
+    if (GT) {   // K of step p+3, V of step p+1 may be pooled tiles (rows of D elements)
+      if (pooled_step(phase_now + 1)) vdma_base = vg_slab + sb * C::kKT * 2 + ev_cur;
+      if (pooled_step(phase_now + 3)) {
+        kdma_base = kg_slab + sb * C::kKT * (D * 2) + ek_cur;
+#pragma unroll
+        for (int i = 0; i < kInstrK; ++i)
+          kdma_off[i] = copy_k.off[i] - (uint32_t)copy_k.row_of(i) * (pitch_bytes - D * 2);
+        return;   // pooled rows are padded to whole blocks: never ragged
+      }
+    }
     if (ek_cur == k_tail[sb]) {
       int lim = a.L - 1 - (last_row0 + sb * C::kKT);
       if (lim < 0) {
@@ -482,11 +556,10 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   // i-th load of this wavefront's share of the batch of phase R: K of step R+3, V of step R+1
   auto dma_one = [&](auto r_tag, int i) __attribute__((always_inline)) {
     constexpr int R = decltype(r_tag)::value;
-    constexpr int sb = (R + 1) % C::kSub;
     if (i < kInstrK)
-      lds_dma16_sv(kdma_base, kdma_off[i], ldsK_addr + ((R + 3) & 3) * C::kKElems * 2 + copy_k.lds_chunk(i));
+      lds_dma16_sv<GT>(kdma_base, kdma_off[i], ldsK_addr + ((R + 3) & 3) * C::kKElems * 2 + copy_k.lds_chunk(i));
     else
-      copy_v.issue_one_at(i - kInstrK, ldsV_addr + ((R + 1) & 3) * C::kVElems * 2, v_base[sb] + ev_cur);
+      copy_v.template issue_one_at<GT>(i - kInstrK, ldsV_addr + ((R + 1) & 3) * C::kVElems * 2, vdma_base);
   };
   // (idle phases) matrix_slot: this group is the phase's matrix group
   auto dma_idle = [&](auto r_tag, bool matrix_slot) __attribute__((always_inline)) {
@@ -572,7 +645,20 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     };
     __builtin_amdgcn_s_setprio(3);
     if (!kSplitCopies) dma_prepare(r_tag);
-    if (ev_older == v_tail[sb]) {
+    float bias = 0.f;   // added to the scaled scores of pooled keys (log2 domain)
+    if (GT && pooled_step(phase_now - 1)) {
+      bias = a.bias_log2;
+      const int key0 = (int)(ev_older / v_tile_bytes) * BLK + sb * C::kKT;
+      if (key0 + C::kKT > a.Lg) {
+#pragma unroll
+        for (int mt = 0; mt < C::kKT / 32; ++mt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            int key = key0 + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
+            if (key >= a.Lg) sacc[mt][i] = -INFINITY;
+          }
+      }
+    } else if (ev_older == v_tail[sb]) {
       const int key0 = last_row0 + sb * C::kKT;
 #pragma unroll
       for (int mt = 0; mt < C::kKT / 32; ++mt)
@@ -588,7 +674,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[mt][i]);
     request(kPortion);
-    mx = fmaxf(mx, swap_halves(mx)) * c;
+    mx = fmaxf(mx, swap_halves(mx)) * c + bias;
     if (__any(mx > m_run)) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = fast_exp2(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
@@ -600,7 +686,7 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
         for (int i = 0; i < 16; ++i) oacc[dm][i] *= alpha;
     }
     request(kPortion);
-    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    const float m_use = ((m_run == -INFINITY) ? 0.f : m_run) - bias;
     float lsum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < C::kKT / 32; ++mt) {
@@ -744,12 +830,17 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   // slabs span 4 GiB or more take the single-stage kernel.  (ASA_FWD_PLAIN=1 forces the latter:
   // used to compare the two.)
   const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
-  if (fits32 && !getenv("ASA_FWD_PLAIN")) {
+  if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb)) return hipErrorNotSupported;
+  if (fits32 && (a.Nbg > 0 || !getenv("ASA_FWD_PLAIN"))) {
     using P = PpCfg<BLK, D>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
+    const void *fn = a.Nbg > 0 ? reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, true>)
+                               : reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, false>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((fwd_pp_kernel<BLK, D>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
+    if (a.Nbg > 0)
+      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, true>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
+    else
+      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, false>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((fwd_kernel<BLK, D, false>), dim3(grid), dim3(C::kThreads), lds, st, a);
@@ -758,8 +849,13 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
 
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
                       const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
-                      float *lse, hipStream_t st) {
+                      float *lse, hipStream_t st, const GlobalTokens *gt) {
   FwdArgs a;
+  a.kg = gt ? gt->kg : nullptr;
+  a.vgt = gt ? reinterpret_cast<const bf16 *>(gt->vgt) : nullptr;
+  a.Lg = gt ? gt->Lg : 0;
+  a.Nbg = gt ? gt->Nbg : 0;
+  a.bias_log2 = gt ? log2f((float)gt->n) : 0.f;
   a.q = q; a.k = k; a.vt = reinterpret_cast<const bf16 *>(vt);
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.o = o; a.o_lo = o_lo; a.lse = lse;
   a.tq = pb.q; a.tk = pb.k; a.to = pb.o;

@@ -54,11 +54,26 @@ __device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
 // with an explicit vmcnt before reading the LDS image, and a kernel that uses this form uses
 // it for all of its direct loads (M0 is written here).
 // lds_byte_addr is the wave-uniform LDS address (lds_addr_of() of the LDS array + offset).
+// FORCE = false leaves the operands as the compiler has them (it must then know them to be
+// uniform, or the assembler rejects the instruction).
+template <bool FORCE = true>
 __device__ __forceinline__ void lds_dma16_sv(const void *uniform_base, uint32_t lane_off,
                                              uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
+  if (!FORCE) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_off), "s"(uniform_base), "s"(lds_byte_addr) : "memory");
+    return;
+  }
+  // (readfirstlane costs nothing where the compiler already knows the value to be uniform and
+  // puts it into scalar registers where it does not)
+  const uint64_t b = reinterpret_cast<uint64_t>(uniform_base);
+  // (the builtin returns a signed int: widen through uint32_t, or the low half sign-extends
+  // into the high one)
+  const uint64_t bu = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b) |
+                      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(lane_off), "s"(uniform_base), "s"(lds_byte_addr) : "memory");
+               :: "v"(lane_off), "s"(bu), "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
 #endif
 }
 // LDS byte address of an object that the compiler knows to live in LDS (apply it to the
@@ -172,8 +187,9 @@ struct ColTileCopy {
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
   }
+  template <bool FORCE = true>
   __device__ __forceinline__ void issue_one_at(int i, uint32_t stage, const char *base) const {
-    lds_dma16_sv(base, off[i], stage + (wave * kInstr + i) * 1024);
+    lds_dma16_sv<FORCE>(base, off[i], stage + (wave * kInstr + i) * 1024);
   }
 };
 
