@@ -179,6 +179,19 @@ int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, con
                    void *hip_stream);
 
 /*
+ * Backward of ASA_G with the mask held constant.  o, o_lo, lse are asa_attn_fwd_g's outputs.
+ * dq, dk, dv [B, H, L, d] bf16 hold the complete gradients: dk and dv include what flows back
+ * through the pooling, the gradient of pooled token w divided by the number of tokens of its
+ * window, added in fp32 before the one rounding to bf16.  Workspace: asa_bwd_g_workspace_bytes.
+ */
+size_t asa_bwd_g_workspace_bytes(const asa_params *p, int n);
+int asa_attn_bwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,
+                   const void *kg, const void *vg, const void *o, const void *o_lo, const void *d_o,
+                   const float *lse, const int32_t *row_ptr, const int32_t *col_idx,
+                   const int32_t *col_ptr, const int32_t *row_idx, void *dq, void *dk, void *dv,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Profiling hook for benchmarks.  Arms the calling thread so that the NEXT asa_attn_fwd,
  * asa_attn_bwd or asa_build_mask call records `start_event` immediately before and
  * `stop_event` immediately after its dominant kernel(s) -- the tile loop of the forward, the

@@ -39,7 +39,8 @@ EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_wo
            "asa_fwd_workspace_bytes", "asa_bwd_workspace_bytes", "asa_build_mask",
            "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd", "asa_attn_bwd",
            "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
-           "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g"]
+           "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
+           "asa_attn_bwd_g"]
 
 
 def load():
@@ -64,13 +65,15 @@ def load():
     L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.asa_attn_bwd.argtypes = [pp] + [vp] * 15 + [ctypes.c_size_t, vp]
     L.asa_set_kernel_timing.argtypes = [vp, vp]
-    for n in ("asa_global_token_count", "asa_fwd_g_workspace_bytes"):
+    for n in ("asa_global_token_count", "asa_fwd_g_workspace_bytes", "asa_bwd_g_workspace_bytes"):
         getattr(L, n).restype = ctypes.c_size_t
         getattr(L, n).argtypes = [pp, ctypes.c_int]
     L.asa_global_tokens.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp]
     L.asa_attn_fwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 11 + [ctypes.c_size_t, vp]
+    L.asa_attn_bwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 17 + [ctypes.c_size_t, vp]
     for n in ("asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
-              "asa_attn_bwd", "asa_set_kernel_timing", "asa_global_tokens", "asa_attn_fwd_g"):
+              "asa_attn_bwd", "asa_set_kernel_timing", "asa_global_tokens", "asa_attn_fwd_g",
+              "asa_attn_bwd_g"):
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -208,6 +211,20 @@ def asa_attn_fwd_g(p: Params, n: int, q, k, v, kg, vg, row_ptr, col_idx, o, lse,
                                  _ptr(vg), _ptr(row_ptr), _ptr(col_idx), _ptr(o), _ptr(o_lo),
                                  _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)),
            "asa_attn_fwd_g")
+
+
+def asa_bwd_g_workspace_bytes(p: Params, n: int) -> int:
+    return int(load().asa_bwd_g_workspace_bytes(ctypes.byref(p.c()), n))
+
+
+def asa_attn_bwd_g(p: Params, n: int, q, k, v, kg, vg, o, d_o, lse, row_ptr, col_idx, col_ptr,
+                   row_idx, dq, dk, dv, workspace, o_lo=None, stream=None):
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().asa_attn_bwd_g(ctypes.byref(p.c()), n, _ptr(q), _ptr(k), _ptr(v), _ptr(kg),
+                                 _ptr(vg), _ptr(o), _ptr(o_lo), _ptr(d_o), _ptr(lse), _ptr(row_ptr),
+                                 _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx), _ptr(dq), _ptr(dk),
+                                 _ptr(dv), _ptr(workspace), ws_bytes, _stream(stream)),
+           "asa_attn_bwd_g")
 
 
 def asa_set_kernel_timing(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):

@@ -306,6 +306,42 @@ int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, con
   return finish(e);
 }
 
+size_t asa_bwd_g_workspace_bytes(const asa_params *p, int n) {
+  Problem pb;
+  int Lg, Nbg;
+  if (resolve(p, &pb) != ASA_OK || global_dims(pb, n, &Lg, &Nbg) != ASA_OK) return 0;
+  return bwd_g_workspace_bytes(pb, Nbg);
+}
+
+int asa_attn_bwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,
+                   const void *kg, const void *vg, const void *o, const void *o_lo, const void *d_o,
+                   const float *lse, const int32_t *row_ptr, const int32_t *col_idx,
+                   const int32_t *col_ptr, const int32_t *row_idx, void *dq, void *dk, void *dv,
+                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  int Lg, Nbg;
+  rc = global_dims(pb, n, &Lg, &Nbg);
+  if (rc != ASA_OK) return rc;
+  {
+    const int n_lists = (row_ptr != nullptr) + (col_idx != nullptr) + (col_ptr != nullptr) + (row_idx != nullptr);
+    if (n_lists != 0 && n_lists != 4) return ASA_ERR_INVALID_ARG;
+  }
+  if (!q || !k || !v || !kg || !vg || !o || !d_o || !lse || !dq || !dk || !dv) return ASA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(kg) || !aligned16(vg) ||
+      !aligned16(o) || !aligned16(o_lo) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) ||
+      !aligned16(dv) || !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx) ||
+      !aligned4(col_ptr) || !aligned4(row_idx))
+    return ASA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < bwd_g_workspace_bytes(pb, Nbg) || !aligned16(workspace))
+    return ASA_ERR_WORKSPACE;
+  GlobalTokens gt;
+  gt.n = n; gt.Lg = Lg; gt.Nbg = Nbg; gt.kg = kg; gt.vg = vg; gt.vgt = nullptr;
+  return finish(launch_bwd(pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
+                           dv, workspace, reinterpret_cast<hipStream_t>(hip_stream), &gt));
+}
+
 int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
                  const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,

@@ -69,6 +69,18 @@ struct BwdArgs {
   TensorView tq, tk, tv, to;
   int H, L, Lpad, Nb, n_slabs;
   float scale, scale_log2e;
+  // ---- global tokens of ASA_G (all zero / null when they are not used)
+  // dK/dV kernels: the key side of a launch may be the pooled tokens instead of K, V
+  int Lk, Nbk;            // valid key rows and key blocks of this launch (= L, Nb normally)
+  float key_bias_log2;    // added to the scaled scores of this launch's keys (log2 domain)
+  float *gk32, *gv32;     // non-null: write fp32 gradients [slab][Nbk * block][d] here instead of dk / dv
+  const float *pool_gk, *pool_gv;   // non-null: add pool_g*[slab][row / pool_n] / count(window) to row's gradient
+  int pool_n, pool_rows;  // pooling window; rows per slab of pool_gk / pool_gv
+  // dQ kernel: pooled tiles appended to every query block's list
+  const void *kg, *vg;    // [slab][Nbg * block][d] bf16
+  const bf16 *kgt;        // [slab][Nbg][d][block]
+  int Lg, Nbg;
+  float pooled_bias_log2;
 };
 
 template <int BLK, int D>
@@ -89,7 +101,8 @@ struct BwdCfg {
 // workgroup copies K rows, V rows and the matching K^T slice straight into LDS; two
 // workgroups share a CU, so one computes while the other's copies are in flight.
 // ---------------------------------------------------------------------------------------
-template <int BLK, int D>
+// GT: with the pooled (global) tokens of ASA_G appended to every query block's list
+template <int BLK, int D, bool GT>
 __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   using C = BwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
@@ -113,11 +126,17 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   const bf16 *kts = a.kt + (int64_t)slab * D * a.Lpad;
   const bool dense = a.row_ptr == nullptr;   // no index lists: every key block
   const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
-  const int n_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  const int n_own_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
+  const int n_tiles = n_own_tiles + (GT ? a.Nbg : 0);   // pooled blocks come after the row's own list
   {
     const int32_t *g = a.col_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) cols[t] = dense ? t : g[t];
+    for (int t = tid; t < n_tiles; t += C::kThreads)
+      cols[t] = t >= n_own_tiles ? t - n_own_tiles : (dense ? t : g[t]);
   }
+  // pooled keys / values of this slab: rows of D elements, transposed tiles like K^T's
+  const bf16 *kgs = reinterpret_cast<const bf16 *>(a.kg) + (int64_t)slab * a.Nbg * BLK * D;
+  const bf16 *vgs = reinterpret_cast<const bf16 *>(a.vg) + (int64_t)slab * a.Nbg * BLK * D;
+  const bf16 *kgts = a.kgt + (int64_t)slab * a.Nbg * D * BLK;
 
   const int qrow = qb * BLK + wave * 32 + n;
   const bool qvalid = qrow < a.L;
@@ -143,6 +162,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   copy_k.init(wave, lane, a.tk.sL);
   copy_v.init(wave, lane, a.tv.sL);
   copy_kt.init(wave, lane);
+  RowTileCopy<C::kST, D, C::kWaves> copy_pooled;   // rows of the pooled tensors (pitch D)
+  if (GT) copy_pooled.init(wave, lane, D);
 
   // A fragments: rows kappa(n) of a 32-key group (K, V), rows rho(n) of a 32-channel group (K^T)
   const int kr = kappa_b(n), cr = rho_b(n);
@@ -158,12 +179,21 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     const int j = cols[step / C::kSub];
     const int sub = step % C::kSub;
     const int key0 = j * BLK + sub * C::kST;
-    copy_k.issue(Ks, ks, key0, a.L);
-    copy_v.issue(Vs, vs, key0, a.L);
-    copy_kt.issue(Kt, kts + (int64_t)j * D * BLK, sub * C::kST);
+    const bool pooled = GT && step >= n_own_tiles * C::kSub;
+    if (pooled) {
+      copy_pooled.issue(Ks, kgs, key0, a.Nbg * BLK);   // padded to whole blocks: never ragged
+      copy_pooled.issue(Vs, vgs, key0, a.Nbg * BLK);
+      copy_kt.issue(Kt, kgts + (int64_t)j * D * BLK, sub * C::kST);
+    } else {
+      copy_k.issue(Ks, ks, key0, a.L);
+      copy_v.issue(Vs, vs, key0, a.L);
+      copy_kt.issue(Kt, kts + (int64_t)j * D * BLK, sub * C::kST);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
-    const bool tail = key0 + C::kST > a.L;
+    const int key_end = pooled ? a.Lg : a.L;   // keys at or past it do not exist
+    const bool tail = key0 + C::kST > key_end;
+    const float lse_b = pooled ? lse2 - a.pooled_bias_log2 : lse2;
 #pragma unroll
     for (int mt = 0; mt < C::kST / 32; ++mt) {
       __builtin_amdgcn_s_setprio(0);
@@ -181,12 +211,12 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
       __builtin_amdgcn_s_setprio(3);   // vector work goes ahead of the other workgroup's MFMA stream
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        float p0 = fast_exp2(fmaf(sacc[i], c, -lse2));
-        float p1 = fast_exp2(fmaf(sacc[i + 1], c, -lse2));
+        float p0 = fast_exp2(fmaf(sacc[i], c, -lse_b));
+        float p1 = fast_exp2(fmaf(sacc[i + 1], c, -lse_b));
         if (tail) {
           int key = key0 + mt * 32 + 16 * (i >> 3) + 8 * hl + (i & 7);
-          if (key >= a.L) p0 = 0.f;
-          if (key + 1 >= a.L) p1 = 0.f;
+          if (key >= key_end) p0 = 0.f;
+          if (key + 1 >= key_end) p1 = 0.f;
         }
         dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - delta), p1 * (pacc[i + 1] - delta));
       }
@@ -242,10 +272,10 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   float *sDelta = sLse + C::kST;
   __shared__ int rows[kMaxNb];
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nbk);
   if (work < 0) return;
-  const int slab = work / a.Nb;
-  const int kb = work - slab * a.Nb;
+  const int slab = work / a.Nbk;
+  const int kb = work - slab * a.Nbk;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, hl = lane >> 5, n = lane & 31;
@@ -265,8 +295,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   }
 
   const int krow = kb * BLK + wave * 32 + n;
-  const bool kvalid = krow < a.L;
-  const int krow_c = kvalid ? krow : a.L - 1;
+  const bool kvalid = krow < a.Lk;
+  const int krow_c = kvalid ? krow : a.Lk - 1;
   bf16x8 kreg[D / 16], vreg[D / 16];
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
@@ -309,7 +339,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     if (tid < C::kST) {
       const int r = q0 + tid;
       const bool ok = r < a.L;
-      sLse[tid] = ok ? a.lse[(int64_t)slab * a.L + r] * kLog2e : INFINITY;
+      sLse[tid] = ok ? a.lse[(int64_t)slab * a.L + r] * kLog2e - a.key_bias_log2 : INFINITY;
       if (DO_DK) sDelta[tid] = ok ? a.delta[(int64_t)slab * a.L + r] : 0.f;
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -372,16 +402,52 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     }
   }
 
+  const float mul = DO_DV ? 1.f : a.scale;
+  float *out32 = DO_DV ? a.gv32 : a.gk32;
+  if (out32) {
+    // gradients of pooled tokens: kept in fp32 for the launch that spreads them over the windows
+    if (kvalid) {
+      float *row = out32 + ((int64_t)slab * a.Nbk * BLK + krow) * D;
+#pragma unroll
+      for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 v = {gacc[dm][4 * q4] * mul, gacc[dm][4 * q4 + 1] * mul, gacc[dm][4 * q4 + 2] * mul,
+                     gacc[dm][4 * q4 + 3] * mul};
+          *reinterpret_cast<f32x4 *>(row + dm * 32 + 16 * hl + 4 * q4) = v;
+        }
+    }
+    return;
+  }
   if (kvalid) {
     bf16 *out_row = DO_DV ? slab_ptr(a.dv, a.tv, slab, a.H) + (int64_t)krow * a.tv.sL
                           : slab_ptr(a.dk, a.tk, slab, a.H) + (int64_t)krow * a.tk.sL;
-    const float mul = DO_DV ? 1.f : a.scale;
+    const float *pool = DO_DV ? a.pool_gv : a.pool_gk;
+#pragma unroll
+    for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) gacc[dm][i] *= mul;
+    if (pool) {
+      // the mean over a window passes 1 / count of the pooled token's gradient to each token
+      const int w = krow / a.pool_n;
+      const int cnt = min(a.pool_n, a.Lk - w * a.pool_n);
+      const float inv = 1.f / (float)cnt;
+      const float *prow = pool + ((int64_t)slab * a.pool_rows + w) * D;
+#pragma unroll
+      for (int dm = 0; dm < D / 32; ++dm)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 v = *reinterpret_cast<const f32x4 *>(prow + dm * 32 + 16 * hl + 4 * q4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gacc[dm][4 * q4 + e] += v[e] * inv;
+        }
+    }
 #pragma unroll
     for (int dm = 0; dm < D / 32; ++dm) {
       uint32_t w[8];
 #pragma unroll
       for (int i = 0; i < 16; i += 2)
-        w[i >> 1] = pack_bf16x2(gacc[dm][i] * mul, gacc[dm][i + 1] * mul);
+        w[i >> 1] = pack_bf16x2(gacc[dm][i], gacc[dm][i + 1]);
       uint4 *po = reinterpret_cast<uint4 *>(out_row + dm * 32 + 16 * hl);
       po[0] = make_uint4(w[0], w[1], w[2], w[3]);
       po[1] = make_uint4(w[4], w[5], w[6], w[7]);
@@ -399,14 +465,24 @@ size_t bwd_workspace_bytes(const Problem &pb) {
   // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32
   return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float));
 }
+static size_t pooled_rows_bytes(const Problem &pb, int Nbg, size_t elem) {
+  return round256((size_t)pb.n_slabs * Nbg * pb.block * pb.d * elem);
+}
+size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg) {
+  // ... then the pooled keys' transposed tiles (bf16) and the pooled tokens' dK, dV (fp32)
+  return bwd_workspace_bytes(pb) + pooled_rows_bytes(pb, Nbg, 2) + 2 * pooled_rows_bytes(pb, Nbg, 4);
+}
 
 template <int BLK, int D>
-static hipError_t launch_bwd_t(const BwdArgs &a, hipStream_t st) {
+static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, hipStream_t st) {
   using C = BwdCfg<BLK, D>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 0>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDvLds);
@@ -417,15 +493,32 @@ static hipError_t launch_bwd_t(const BwdArgs &a, hipStream_t st) {
     attr_set = true;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
+  hipError_t e = hipSuccess;
   timing_begin(st);
-  hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(grid), dim3(C::kThreads), C::kDvLds, st, a);
-  hipError_t e = hipGetLastError();
+  if (pooled_launch) {
+    // gradients of the pooled tokens first (fp32, every query block attends them) ...
+    const int ggrid = xcd_grid(pooled_launch->n_slabs * pooled_launch->Nbk);
+    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, *pooled_launch);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, *pooled_launch);
+      e = hipGetLastError();
+    }
+  }
+  // ... then the tokens' own gradients, which add their share of the pooled ones
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(grid), dim3(C::kThreads), C::kDvLds, st, a);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess) {
     hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(grid), dim3(C::kThreads), C::kDkLds, st, a);
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
-    hipLaunchKernelGGL((dq_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
+    if (pooled_launch)
+      hipLaunchKernelGGL((dq_kernel<BLK, D, true>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
+    else
+      hipLaunchKernelGGL((dq_kernel<BLK, D, false>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
     e = hipGetLastError();
   }
   timing_end(st);
@@ -436,7 +529,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
                       const void *o, const void *o_lo, const void *d_o, const float *lse,
                       const int32_t *row_ptr, const int32_t *col_idx, const int32_t *col_ptr,
                       const int32_t *row_idx, void *dq, void *dk, void *dv, void *workspace,
-                      hipStream_t st) {
+                      hipStream_t st, const GlobalTokens *gt) {
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
   const size_t tb = transposed_bytes(pb);
   bf16 *qt = reinterpret_cast<bf16 *>(ws);
@@ -470,10 +563,38 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   a.H = pb.H; a.L = pb.L; a.Lpad = pb.Lpad; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs;
   a.scale = pb.scale;
   a.scale_log2e = pb.scale * kLog2e;
-  if (pb.block == 128 && pb.d == 128) return launch_bwd_t<128, 128>(a, st);
-  if (pb.block == 128 && pb.d == 64) return launch_bwd_t<128, 64>(a, st);
-  if (pb.block == 64 && pb.d == 128) return launch_bwd_t<64, 128>(a, st);
-  if (pb.block == 64 && pb.d == 64) return launch_bwd_t<64, 64>(a, st);
+  a.Lk = pb.L; a.Nbk = pb.Nb; a.key_bias_log2 = 0.f;
+  a.gk32 = a.gv32 = nullptr; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
+  a.kg = a.vg = nullptr; a.kgt = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
+  BwdArgs g;                       // the launch whose key side is the pooled tokens
+  const BwdArgs *pooled = nullptr;
+  if (gt) {
+    unsigned char *wg = ws + bwd_workspace_bytes(pb);
+    bf16 *kgt = reinterpret_cast<bf16 *>(wg);
+    float *gk32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2));
+    float *gv32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2) +
+                                            pooled_rows_bytes(pb, gt->Nbg, 4));
+    Problem pg = pb;               // the pooled tensors as a problem of their own
+    pg.L = gt->Lg; pg.Nb = gt->Nbg; pg.Lpad = gt->Nbg * pb.block;
+    TensorView tvg;
+    tvg.sL = pb.d; tvg.sH = (int64_t)pg.Lpad * pb.d; tvg.sB = tvg.sH * pb.H;
+    e = launch_transpose(pg, gt->kg, tvg, kgt, st);
+    if (e != hipSuccess) return e;
+    const float bias = log2f((float)gt->n);
+    g = a;
+    g.k = gt->kg; g.v = gt->vg; g.tk = tvg; g.tv = tvg;
+    g.col_ptr = nullptr; g.row_idx = nullptr;          // every query block attends the pooled tokens
+    g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.key_bias_log2 = bias;
+    g.gk32 = gk32; g.gv32 = gv32;
+    pooled = &g;
+    a.pool_gk = gk32; a.pool_gv = gv32; a.pool_n = gt->n; a.pool_rows = gt->Nbg * pb.block;
+    a.kg = gt->kg; a.vg = gt->vg; a.kgt = kgt; a.Lg = gt->Lg; a.Nbg = gt->Nbg;
+    a.pooled_bias_log2 = bias;
+  }
+  if (pb.block == 128 && pb.d == 128) return launch_bwd_t<128, 128>(a, pooled, st);
+  if (pb.block == 128 && pb.d == 64) return launch_bwd_t<128, 64>(a, pooled, st);
+  if (pb.block == 64 && pb.d == 128) return launch_bwd_t<64, 128>(a, pooled, st);
+  if (pb.block == 64 && pb.d == 64) return launch_bwd_t<64, 64>(a, pooled, st);
   return hipErrorInvalidValue;
 }
 

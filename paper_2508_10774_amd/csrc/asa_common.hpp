@@ -76,8 +76,10 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
                       const void *o, const void *o_lo, const void *d_o, const float *lse,
                       const int32_t *row_ptr,
                       const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx,
-                      void *dq, void *dk, void *dv, void *workspace, hipStream_t st);
+                      void *dq, void *dk, void *dv, void *workspace, hipStream_t st,
+                      const GlobalTokens *gt = nullptr);
 size_t bwd_workspace_bytes(const Problem &pb);
+size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg);
 
 #ifdef __HIPCC__
 // ---------------------------------------------------------------- device helpers

@@ -168,3 +168,30 @@ def test_wan_padded_full_density_is_dense_attention():
     kf, vf = (torch.from_numpy(f(x[0, 1]).astype(np.float64)) for x in (kb, vb))
     want = torch.nn.functional.scaled_dot_product_attention(qf[None], kf[None], vf[None])[0].numpy()
     util.assert_close_bf16(util.host_f32(o[0, 1])[rows], want, "dense O")
+
+
+def test_wan_global_tokens_forward_sampled_blocks(wan):
+    """ASA_G at the benchmark's shape and launch configuration (window n = block = 128: 256
+    pooled tokens in two pooled blocks), checked on sampled query blocks of two heads."""
+    from oracle import global_tokens as og
+    p, w, n = wan.p, wan.w, wan.w.block
+    q, k, v = (util.dev_bf16(x) for x in (wan.qb, wan.kb, wan.vb))
+    G = binding.asa_global_token_count(p, n)
+    kg = torch.empty((w.B, w.H, G, w.d), dtype=torch.bfloat16, device="cuda")
+    vg = torch.empty_like(kg)
+    binding.asa_global_tokens(p, n, k, v, kg, vg)
+    bufs = util.lists_from_mask(p, wan.run_mask, with_csc=False)
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B * w.H, w.L), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(binding.asa_fwd_g_workspace_bytes(p, n))
+    binding.asa_attn_fwd_g(p, n, q, k, v, kg, vg, bufs["row_ptr"], bufs["col_idx"], o, lse, ws)
+    torch.cuda.synchronize()
+    Nb = p.Nb
+    for h in (0, 7):
+        qf, kf, vf, _ = wan.slab(h)
+        blocks = [0, 97, Nb - 1]
+        want, wl = og.attn_fwd_g(qf, kf, vf, wan.run_mask[h], w.block, n, None, blocks)
+        rows = ~np.isnan(wl)
+        e = util.assert_close_bf16(util.host_f32(o[0, h])[rows], want[rows], f"wan ASA_G O head {h}")
+        assert np.abs(lse[h].cpu().numpy()[rows] - wl[rows]).max() <= util.LSE_ABS
+        print(f"[fullsize] wan ASA_G O head {h}: scaled max {e[0]:.2e} mean {e[1]:.2e}", flush=True)

@@ -94,3 +94,54 @@ def test_fwd_global_tokens_dense_lists_and_residual():
     # o + o_lo carries about 16 significant bits of the fp32 result
     both = util.host_f32(o)[0, 0].astype(np.float64) + util.host_f32(lo)[0, 0]
     assert np.abs(both - want_o).max() < 2e-3
+
+
+def _run_bwd_g(p, n, q, k, v, g, bufs):
+    o, lse, o_lo, kg, vg = _run_fwd_g(p, n, q, k, v, bufs, with_lo=True)
+    dq = torch.full_like(q, float("nan"))
+    dk = torch.full_like(k, float("nan"))
+    dv = torch.full_like(v, float("nan"))
+    ws = binding.alloc_workspace(binding.asa_bwd_g_workspace_bytes(p, n))
+    binding.asa_attn_bwd_g(p, n, q, k, v, kg, vg, o, g, lse, bufs["row_ptr"], bufs["col_idx"],
+                           bufs["col_ptr"], bufs["row_idx"], dq, dk, dv, ws, o_lo=o_lo)
+    torch.cuda.synchronize()
+    return [util.host_f32(x) for x in (dq, dk, dv)]
+
+
+@pytest.mark.parametrize("B,H,L,d,block,n,dens", [
+    (1, 2, 1024, 64, 64, 64, 0.4),
+    (1, 2, 1000, 128, 128, 128, 0.5),    # ragged last block and last window
+    (2, 1, 300, 64, 128, 16, 0.6),
+    (1, 1, 520, 128, 64, 8, 0.5),        # two pooled blocks
+])
+def test_bwd_global_tokens(B, H, L, d, block, n, dens):
+    print(f"case B={B} H={H} L={L} d={d} block={block} n={n} dens={dens}", flush=True)
+    p = binding.Params(B=B, H=H, L=L, d=d, block=block)
+    qb, kb, vb, gb = (synth.make_iid((B, H, L, d), L + d + n, s) for s in range(4))
+    mask = synth.random_block_mask(p.Nb, dens, seed=L, slabs=B * H)
+    mask[0, 0, :] = 0                     # a query block that sees the pooled tokens only
+    mask[0, :, -1] = 0                    # a key block that gets gradient through the pooling only
+    bufs = util.lists_from_mask(p, mask)
+    dq, dk, dv = _run_bwd_g(p, n, *(util.dev_bf16(x) for x in (qb, kb, vb, gb)), bufs)
+    qf, kf, vf, gf = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb, gb))
+    m3 = mask.reshape(-1, p.Nb, p.Nb)
+    for b in range(B):
+        for h in range(H):
+            wq, wk, wv = og.attn_bwd_g(qf[b, h], kf[b, h], vf[b, h], gf[b, h], m3[b * H + h], block, n)
+            eq = util.assert_close_bf16(dq[b, h], wq, f"dQ[{b},{h}]")
+            ek = util.assert_close_bf16(dk[b, h], wk, f"dK[{b},{h}]")
+            ev = util.assert_close_bf16(dv[b, h], wv, f"dV[{b},{h}]")
+            print(f"  slab {b},{h}: max-abs dQ {eq[0]:.2e} dK {ek[0]:.2e} dV {ev[0]:.2e}", flush=True)
+
+
+def test_bwd_global_tokens_dense_lists():
+    p = binding.Params(B=1, H=1, L=384, d=64, block=64)
+    n = 32
+    qb, kb, vb, gb = (synth.make_iid((1, 1, 384, 64), 5, s) for s in range(4))
+    t = [util.dev_bf16(x) for x in (qb, kb, vb, gb)]
+    full = util.lists_from_mask(p, np.ones((1, 6, 6), np.uint8))
+    none = {"row_ptr": None, "col_idx": None, "col_ptr": None, "row_idx": None}
+    want = _run_bwd_g(p, n, *t, full)
+    got = _run_bwd_g(p, n, *t, none)
+    for a, b, name in zip(got, want, ("dQ", "dK", "dV")):
+        assert np.array_equal(a, b), name
