@@ -2,7 +2,7 @@
 """Benchmark of the ASA hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan|cog|wan-padded]
-                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref]
+                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref] [--no-asa-g]
 
 One step = one pass of the whole path over one batch of seeded synthetic video-token tensors
 that are already resident in HBM: mask generation (asa_build_mask), block-sparse forward
@@ -49,6 +49,7 @@ def parse():
     ap.add_argument("--no-bwd", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-ref", action="store_true")
+    ap.add_argument("--no-asa-g", action="store_true")
     ap.add_argument("--cpu-sample-slabs", type=int, default=3)
     return ap.parse_args()
 
@@ -142,6 +143,33 @@ def main():
         torch.cuda.synchronize()
         dense_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[1:]]))
 
+    # ASA_G (global tokens, window n = block): pooling + forward + backward, outside the timed steps
+    asa_g = None
+    if not args.no_asa_g and not args.no_bwd:
+        n_win = p.block
+        G = binding.asa_global_token_count(p, n_win)
+        kg = torch.empty((p.B, p.H, G, p.d), dtype=torch.bfloat16, device="cuda")
+        vg = torch.empty_like(kg)
+        ws_fg = binding.alloc_workspace(binding.asa_fwd_g_workspace_bytes(p, n_win))
+        ws_bg = binding.alloc_workspace(binding.asa_bwd_g_workspace_bytes(p, n_win))
+        g_ev = [[ev() for _ in range(4)] for _ in range(4)]
+        for e4 in g_ev:
+            e4[0].record(stream)
+            binding.asa_global_tokens(p, n_win, k, v, kg, vg)
+            e4[1].record(stream)
+            binding.asa_attn_fwd_g(p, n_win, q, k, v, kg, vg, bufs["row_ptr"], bufs["col_idx"], o, lse,
+                                   ws_fg, o_lo=o_lo)
+            e4[2].record(stream)
+            binding.asa_attn_bwd_g(p, n_win, q, k, v, kg, vg, o, g, lse, bufs["row_ptr"],
+                                   bufs["col_idx"], bufs["col_ptr"], bufs["row_idx"], dq, dk, dv,
+                                   ws_bg, o_lo=o_lo)
+            e4[3].record(stream)
+        torch.cuda.synchronize()
+        med = lambda i: float(np.median([e4[i].elapsed_time(e4[i + 1]) for e4 in g_ev[1:]]))
+        asa_g = {"window": n_win, "pooled_tokens": int(-(-p.L // n_win)),
+                 "pool_ms": round(med(0), 4), "fwd_ms": round(med(1), 4), "bwd_ms": round(med(2), 4)}
+        del ws_fg, ws_bg
+
     mask_ms = np.array([e["s0"].elapsed_time(e["s1"]) for e in per_step])
     fwd_ms = np.array([e["s1"].elapsed_time(e["s2"]) for e in per_step])
     bwd_ms = np.array([e["s2"].elapsed_time(e["s3"]) for e in per_step])
@@ -195,6 +223,7 @@ def main():
             p.B * p.H * p.Nb * p.Nb * tile_flops / (dense_ms * 1e-3) / 1e12, 2),
         "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
+        "asa_g": asa_g,
         "roofline": {
             "kernel": f"fwd_pp_kernel<{p.block},{p.d}>",
             "bound": "mfma",

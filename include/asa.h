@@ -169,8 +169,8 @@ int asa_global_tokens(const asa_params *p, int n, const void *k, const void *v, 
 /*
  * Forward of ASA_G: as asa_attn_fwd with the pooled keys / values kg, vg of window n appended
  * (NULL index lists: dense over the original keys, plus the pooled ones).  LSE covers both
- * parts.  Workspace: asa_fwd_g_workspace_bytes.  Tensors whose (batch, head) slab of K spans
- * 4 GiB or more are ASA_ERR_UNSUPPORTED here.
+ * parts.  Workspace: asa_fwd_g_workspace_bytes.  ASA_ERR_UNSUPPORTED here: a (batch, head) slab
+ * of K spanning 4 GiB or more, and K rows that are not contiguous (k_stride[2] != d).
  */
 size_t asa_fwd_g_workspace_bytes(const asa_params *p, int n);
 int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,

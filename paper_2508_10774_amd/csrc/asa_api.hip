@@ -287,6 +287,7 @@ int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, con
       !aligned16(o) || !aligned16(o_lo) || !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx))
     return ASA_ERR_INVALID_ARG;
   if ((uint64_t)pb.Nb * pb.block * (uint64_t)pb.k.sL * 2u >= 0xFFFFFFFFull) return ASA_ERR_UNSUPPORTED;
+  if (pb.k.sL != pb.d) return ASA_ERR_UNSUPPORTED;   // rows of K must be contiguous here
   if (!workspace || workspace_bytes < transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg) ||
       !aligned16(workspace))
     return ASA_ERR_WORKSPACE;

@@ -73,7 +73,8 @@ struct BwdArgs {
   // dK/dV kernels: the key side of a launch may be the pooled tokens instead of K, V
   int Lk, Nbk;            // valid key rows and key blocks of this launch (= L, Nb normally)
   float key_bias_log2;    // added to the scaled scores of this launch's keys (log2 domain)
-  float *gk32, *gv32;     // non-null: write fp32 gradients [slab][Nbk * block][d] here instead of dk / dv
+  float *gk32, *gv32;     // non-null: write fp32 gradients [chunk][slab][Nbk * block][d] here instead of dk / dv
+  int q_chunks;           // with gk32 / gv32: the query blocks are split into this many ranges, one workgroup each
   const float *pool_gk, *pool_gv;   // non-null: add pool_g*[slab][row / pool_n] / count(window) to row's gradient
   int pool_n, pool_rows;  // pooling window; rows per slab of pool_gk / pool_gv
   // dQ kernel: pooled tiles appended to every query block's list
@@ -272,8 +273,10 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   float *sDelta = sLse + C::kST;
   __shared__ int rows[kMaxNb];
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nbk);
-  if (work < 0) return;
+  const int work_c = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nbk * a.q_chunks);
+  if (work_c < 0) return;
+  const int chunk = work_c % a.q_chunks;      // range of query blocks (1 range unless pooled keys)
+  const int work = work_c / a.q_chunks;
   const int slab = work / a.Nbk;
   const int kb = work - slab * a.Nbk;
   const int tid = threadIdx.x;
@@ -288,10 +291,13 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   const bf16 *gts = a.dot + (int64_t)slab * D * a.Lpad;
   const bool dense = a.col_ptr == nullptr;   // no index lists: every query block
   const int t_begin = dense ? 0 : a.col_ptr[slab * (a.Nb + 1) + kb];
-  const int n_tiles = dense ? a.Nb : a.col_ptr[slab * (a.Nb + 1) + kb + 1] - t_begin;
+  const int per_chunk = (a.Nb + a.q_chunks - 1) / a.q_chunks;
+  const int first = chunk * per_chunk;          // dense: my range of query blocks
+  const int n_tiles = dense ? max(0, min(per_chunk, a.Nb - first))
+                            : a.col_ptr[slab * (a.Nb + 1) + kb + 1] - t_begin;
   {
     const int32_t *g = a.row_idx + (int64_t)slab * a.Nb * a.Nb + t_begin;
-    for (int t = tid; t < n_tiles; t += C::kThreads) rows[t] = dense ? t : g[t];
+    for (int t = tid; t < n_tiles; t += C::kThreads) rows[t] = dense ? first + t : g[t];
   }
 
   const int krow = kb * BLK + wave * 32 + n;
@@ -407,7 +413,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   if (out32) {
     // gradients of pooled tokens: kept in fp32 for the launch that spreads them over the windows
     if (kvalid) {
-      float *row = out32 + ((int64_t)slab * a.Nbk * BLK + krow) * D;
+      float *row = out32 + (((int64_t)chunk * a.n_slabs + slab) * a.Nbk * BLK + krow) * D;
 #pragma unroll
       for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
@@ -465,12 +471,30 @@ size_t bwd_workspace_bytes(const Problem &pb) {
   // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32
   return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float));
 }
+// sum of the per-range partial gradients of the pooled tokens into range 0's buffer
+__global__ void pooled_reduce_kernel(float *buf, int chunks, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  f32x4 acc = reinterpret_cast<const f32x4 *>(buf)[i];
+  for (int c = 1; c < chunks; ++c) {
+    const f32x4 v = reinterpret_cast<const f32x4 *>(buf + c * n * 4)[i];
+    acc += v;
+  }
+  reinterpret_cast<f32x4 *>(buf)[i] = acc;
+}
+static int pooled_chunks(const Problem &pb, int Nbg) {
+  // enough workgroups to fill the chip, at most 16 ranges (each costs a partial buffer)
+  int c = (1024 + pb.n_slabs * Nbg - 1) / (pb.n_slabs * Nbg);
+  c = c > 16 ? 16 : c;
+  return c > pb.Nb ? pb.Nb : (c < 1 ? 1 : c);
+}
 static size_t pooled_rows_bytes(const Problem &pb, int Nbg, size_t elem) {
   return round256((size_t)pb.n_slabs * Nbg * pb.block * pb.d * elem);
 }
 size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg) {
   // ... then the pooled keys' transposed tiles (bf16) and the pooled tokens' dK, dV (fp32)
-  return bwd_workspace_bytes(pb) + pooled_rows_bytes(pb, Nbg, 2) + 2 * pooled_rows_bytes(pb, Nbg, 4);
+  return bwd_workspace_bytes(pb) + pooled_rows_bytes(pb, Nbg, 2) +
+         2 * pooled_chunks(pb, Nbg) * pooled_rows_bytes(pb, Nbg, 4);
 }
 
 template <int BLK, int D>
@@ -497,11 +521,19 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
   timing_begin(st);
   if (pooled_launch) {
     // gradients of the pooled tokens first (fp32, every query block attends them) ...
-    const int ggrid = xcd_grid(pooled_launch->n_slabs * pooled_launch->Nbk);
-    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, *pooled_launch);
+    const BwdArgs &g = *pooled_launch;
+    const int ggrid = xcd_grid(g.n_slabs * g.Nbk * g.q_chunks);
+    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, g);
     e = hipGetLastError();
     if (e == hipSuccess) {
-      hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, *pooled_launch);
+      hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, g);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess && g.q_chunks > 1) {
+      const int64_t n4 = (int64_t)g.n_slabs * g.Nbk * BLK * D / 4;
+      const int rgrid = (int)((n4 + 255) / 256);
+      hipLaunchKernelGGL(pooled_reduce_kernel, dim3(rgrid), dim3(256), 0, st, g.gv32, g.q_chunks, n4);
+      hipLaunchKernelGGL(pooled_reduce_kernel, dim3(rgrid), dim3(256), 0, st, g.gk32, g.q_chunks, n4);
       e = hipGetLastError();
     }
   }
@@ -564,7 +596,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   a.scale = pb.scale;
   a.scale_log2e = pb.scale * kLog2e;
   a.Lk = pb.L; a.Nbk = pb.Nb; a.key_bias_log2 = 0.f;
-  a.gk32 = a.gv32 = nullptr; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
+  a.gk32 = a.gv32 = nullptr; a.q_chunks = 1; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
   a.kg = a.vg = nullptr; a.kgt = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
   BwdArgs g;                       // the launch whose key side is the pooled tokens
   const BwdArgs *pooled = nullptr;
@@ -572,8 +604,9 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     unsigned char *wg = ws + bwd_workspace_bytes(pb);
     bf16 *kgt = reinterpret_cast<bf16 *>(wg);
     float *gk32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2));
+    const int chunks = pooled_chunks(pb, gt->Nbg);
     float *gv32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2) +
-                                            pooled_rows_bytes(pb, gt->Nbg, 4));
+                                            chunks * pooled_rows_bytes(pb, gt->Nbg, 4));
     Problem pg = pb;               // the pooled tensors as a problem of their own
     pg.L = gt->Lg; pg.Nb = gt->Nbg; pg.Lpad = gt->Nbg * pb.block;
     TensorView tvg;
@@ -585,7 +618,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     g.k = gt->kg; g.v = gt->vg; g.tk = tvg; g.tv = tvg;
     g.col_ptr = nullptr; g.row_idx = nullptr;          // every query block attends the pooled tokens
     g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.key_bias_log2 = bias;
-    g.gk32 = gk32; g.gv32 = gv32;
+    g.gk32 = gk32; g.gv32 = gv32; g.q_chunks = chunks;
     pooled = &g;
     a.pool_gk = gk32; a.pool_gv = gv32; a.pool_n = gt->n; a.pool_rows = gt->Nbg * pb.block;
     a.kg = gt->kg; a.vg = gt->vg; a.kgt = kgt; a.Lg = gt->Lg; a.Nbg = gt->Nbg;

@@ -433,6 +433,8 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
   static_assert(kBatchInstr == 4 || kBatchInstr == 8 || kBatchInstr == 16, "unexpected copy size");
   const int kr = kappa(n), cr = rho(n);
   const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  const int k_frag0 = kr * D + kx;          // element offset of my K fragment 0 in a 32-key group
+  const int v_frag0 = cr * C::kKT + cx;     // of my V^T fragment 0 in a 32-channel group
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -468,9 +470,8 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
       const int r = j * BLK + (step % C::kSub) * C::kKT;
       if (pooled_step(step)) {
 #pragma unroll
-        for (int i = 0; i < kInstrK; ++i)
-          lds_dma16_sv(kg_slab + (int64_t)r * (D * 2),
-                       copy_k.off[i] - (uint32_t)copy_k.row_of(i) * (pitch_bytes - D * 2),
+        for (int i = 0; i < kInstrK; ++i)   // (with pooled tokens the rows of K are D elements apart, like theirs)
+          lds_dma16_sv(kg_slab + (int64_t)r * (D * 2), copy_k.off[i],
                        ldsK_addr + step * C::kKElems * 2 + copy_k.lds_chunk(i));
       } else {
         copy_k.issue_at_ragged(ldsK_addr + step * C::kKElems * 2, kb + (int64_t)r * pitch_bytes, a.L - 1 - r);
@@ -533,10 +534,9 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     if (GT) {   // K of step p+3, V of step p+1 may be pooled tiles (rows of D elements)
       if (pooled_step(phase_now + 1)) vdma_base = vg_slab + sb * C::kKT * 2 + ev_cur;
       if (pooled_step(phase_now + 3)) {
+        // the host admits pooled tokens only where K's rows are D elements apart, like theirs:
+        // the per-lane offsets are the same
         kdma_base = kg_slab + sb * C::kKT * (D * 2) + ek_cur;
-#pragma unroll
-        for (int i = 0; i < kInstrK; ++i)
-          kdma_off[i] = copy_k.off[i] - (uint32_t)copy_k.row_of(i) * (pitch_bytes - D * 2);
         return;   // pooled rows are padded to whole blocks: never ragged
       }
     }
@@ -589,17 +589,30 @@ __global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
     const bf16 *Vs = ldsV + ((R + 2) & 3) * C::kVElems;
     const bf16 *Ks = ldsK + R * C::kKElems;
     bf16x8 ring[kRing];
+    int zero = 0;
+    if (GT) asm volatile("s_mov_b32 %0, 0" : "=s"(zero));
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int i = n0; i < n1 + kDepth; ++i) {
       if (i < n1) {
+        // fragment addresses are formed here from two per-lane bases (the swizzle is an XOR of
+        // the low address bits, so (base + x) ^ (16 s) = base + (x ^ 16 s)); `zero` keeps the
+        // compiler from hoisting twelve loop-invariant address registers out of the loop
+        // (only the pooled-token variant, which is short of registers; the other one keeps the
+        // twelve addresses in registers and saves the XORs)
         if (i < kNPv) {
           const int t = i / (D / 32), dm = i % (D / 32);
-          ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Vs + (dm * 32 + cr) * C::kKT + ((16 * t) ^ cx));
+          if (GT)
+            ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Vs + dm * 32 * C::kKT + ((v_frag0 ^ (16 * t)) ^ zero));
+          else
+            ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Vs + (dm * 32 + cr) * C::kKT + ((16 * t) ^ cx));
         } else {
           const int e = i - kNPv, sk = e / (C::kKT / 32), mt = e % (C::kKT / 32);
-          ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Ks + (mt * 32 + kr) * D + ((16 * sk) ^ kx));
+          if (GT)
+            ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Ks + mt * 32 * D + ((k_frag0 ^ (16 * sk)) ^ zero));
+          else
+            ring[i % kRing] = *reinterpret_cast<const bf16x8 *>(Ks + (mt * 32 + kr) * D + ((16 * sk) ^ kx));
         }
       }
       const int c_i = i - kDepth;
@@ -830,7 +843,7 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   // slabs span 4 GiB or more take the single-stage kernel.  (ASA_FWD_PLAIN=1 forces the latter:
   // used to compare the two.)
   const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
-  if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb)) return hipErrorNotSupported;
+  if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb || a.tk.sL != D)) return hipErrorNotSupported;
   if (fits32 && (a.Nbg > 0 || !getenv("ASA_FWD_PLAIN"))) {
     using P = PpCfg<BLK, D>;
     const void *fn = a.Nbg > 0 ? reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, true>)
