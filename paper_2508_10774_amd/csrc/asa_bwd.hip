@@ -69,6 +69,7 @@ struct BwdArgs {
   TensorView tq, tk, tv, to;
   int H, L, Lpad, Nb, n_slabs;
   float scale, scale_log2e;
+  const int32_t *order;   // dK/dV: work item of each workgroup slot, longest column first inside an XCD's share (null: natural order)
   // ---- global tokens of ASA_G (all zero / null when they are not used)
   // dK/dV kernels: the key side of a launch may be the pooled tokens instead of K, V
   int Lk, Nbk;            // valid key rows and key blocks of this launch (= L, Nb normally)
@@ -276,7 +277,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   const int work_c = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nbk * a.q_chunks);
   if (work_c < 0) return;
   const int chunk = work_c % a.q_chunks;      // range of query blocks (1 range unless pooled keys)
-  const int work = work_c / a.q_chunks;
+  const int work = a.order ? a.order[work_c] : work_c / a.q_chunks;
   const int slab = work / a.Nbk;
   const int kb = work - slab * a.Nbk;
   const int tid = threadIdx.x;
@@ -462,14 +463,56 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Order of the dK / dV workgroups.  Columns of the mask differ a lot in length (31..220 query
+// blocks at 25 % density on video-like inputs) and a long one that starts late ends the kernel
+// late.  Each XCD keeps its contiguous share of the (slab, key block) items (they share an L2)
+// but works through it longest column first.  One workgroup per XCD share: bitonic sort of
+// (length descending, item ascending) keys in LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int kOrderMax = 2048;   // items per XCD share that the sort handles
+__global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t *col_ptr, int Nb, int total,
+                                                         int32_t *order) {
+  __shared__ uint64_t key[kOrderMax];
+  const int share = (total + kNumXcd - 1) / kNumXcd;
+  const int first = blockIdx.x * share;
+  const int count = max(0, min(share, total - first));
+  for (int t = threadIdx.x; t < kOrderMax; t += 1024) {
+    uint64_t kk = ~0ull;                       // padding sorts last
+    if (t < count) {
+      const int item = first + t, slab = item / Nb, kb = item - slab * Nb;
+      const uint32_t len = (uint32_t)(col_ptr[slab * (Nb + 1) + kb + 1] - col_ptr[slab * (Nb + 1) + kb]);
+      kk = ((uint64_t)(0xFFFFFFFFu - len) << 32) | (uint32_t)item;
+    }
+    key[t] = kk;
+  }
+  __syncthreads();
+  for (int size = 2; size <= kOrderMax; size <<= 1)
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = threadIdx.x; t < kOrderMax / 2; t += 1024) {
+        const int lo = 2 * t - (t & (stride - 1));       // index with bit `stride` clear
+        const int hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const uint64_t x = key[lo], y = key[hi];
+        if ((x > y) == up) { key[lo] = y; key[hi] = x; }
+      }
+      __syncthreads();
+    }
+  for (int t = threadIdx.x; t < count; t += 1024) order[first + t] = (int32_t)(uint32_t)key[t];
+}
+
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 static size_t transposed_bytes(const Problem &pb) {
   return round256((size_t)pb.n_slabs * pb.d * pb.Lpad * sizeof(uint16_t));
 }
 
+static size_t order_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.Nb * sizeof(int32_t));
+}
 size_t bwd_workspace_bytes(const Problem &pb) {
-  // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32
-  return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float));
+  // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32, then the order of
+  // the dK / dV workgroups
+  return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float)) +
+         order_bytes(pb);
 }
 // sum of the per-range partial gradients of the pooled tokens into range 0's buffer
 __global__ void pooled_reduce_kernel(float *buf, int chunks, int64_t n) {
@@ -568,6 +611,8 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   bf16 *kt = reinterpret_cast<bf16 *>(ws + tb);
   bf16 *dot = reinterpret_cast<bf16 *>(ws + 2 * tb);
   float *delta = reinterpret_cast<float *>(ws + 3 * tb);
+  int32_t *order = reinterpret_cast<int32_t *>(ws + 3 * tb +
+                                               round256((size_t)pb.n_slabs * pb.L * sizeof(float)));
 
   hipError_t e = launch_transpose(pb, q, pb.q, qt, st);
   if (e != hipSuccess) return e;
@@ -595,6 +640,16 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   a.H = pb.H; a.L = pb.L; a.Lpad = pb.Lpad; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs;
   a.scale = pb.scale;
   a.scale_log2e = pb.scale * kLog2e;
+  a.order = nullptr;
+  {
+    const int total = pb.n_slabs * pb.Nb;
+    if (col_ptr && (total + kNumXcd - 1) / kNumXcd <= kOrderMax) {
+      hipLaunchKernelGGL(dkv_order_kernel, dim3(kNumXcd), dim3(1024), 0, st, col_ptr, pb.Nb, total, order);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      a.order = order;
+    }
+  }
   a.Lk = pb.L; a.Nbk = pb.Nb; a.key_bias_log2 = 0.f;
   a.gk32 = a.gv32 = nullptr; a.q_chunks = 1; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
   a.kg = a.vg = nullptr; a.kgt = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
@@ -615,6 +670,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     if (e != hipSuccess) return e;
     const float bias = log2f((float)gt->n);
     g = a;
+    g.order = nullptr;
     g.k = gt->kg; g.v = gt->vg; g.tk = tvg; g.tv = tvg;
     g.col_ptr = nullptr; g.row_idx = nullptr;          // every query block attends the pooled tokens
     g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.key_bias_log2 = bias;
