@@ -102,6 +102,24 @@ int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *m
                    float *p_imp, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * asa_build_mask with seeded random sampling (Alg. 3 step 2, "randomly sample k tokens from
+ * each block", made reproducible): the sample_offsets of `p` are ignored; instead every block
+ * of every (batch, head) slab draws its own k_samples positions with a counter-based generator.
+ * Position j of block blk of slab s = batch * H + head gets the first word of Philox-4x32-10
+ * (Salmon et al., SC'11) with counter (j, blk, s, 0) and key (seed low word, seed high word);
+ * the k_samples positions with the smallest (word, j) are the sample, used in ascending order
+ * for both Q and K.  asa_sample_offsets writes that table alone:
+ *   table [B*H, Nb, k_samples] uint8 (DEVICE).
+ * Workspace of the seeded build: asa_mask_seeded_workspace_bytes.
+ */
+size_t asa_mask_seeded_workspace_bytes(const asa_params *p);
+int asa_build_mask_seeded(const asa_params *p, uint64_t seed, const void *q, const void *k,
+                          uint8_t *mask, int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr,
+                          int32_t *row_idx, float *p_imp, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+int asa_sample_offsets(const asa_params *p, uint64_t seed, uint8_t *table, void *hip_stream);
+
+/*
  * The selection rule alone (Alg. 3 steps 6-11) on caller-supplied scores
  * [B*H, Nb, Nb] fp32 -> mask [B*H, Nb, Nb] uint8 (prefix rows/columns included).
  */

@@ -40,7 +40,8 @@ EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_wo
            "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd", "asa_attn_bwd",
            "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
            "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
-           "asa_attn_bwd_g"]
+           "asa_attn_bwd_g", "asa_mask_seeded_workspace_bytes", "asa_build_mask_seeded",
+           "asa_sample_offsets"]
 
 
 def load():
@@ -56,10 +57,13 @@ def load():
     L.asa_error_string.restype = ctypes.c_char_p
     L.asa_error_string.argtypes = [ctypes.c_int]
     L.asa_last_hip_error.restype = ctypes.c_char_p
-    for n in ("asa_mask_workspace_bytes", "asa_fwd_workspace_bytes", "asa_bwd_workspace_bytes"):
+    for n in ("asa_mask_workspace_bytes", "asa_fwd_workspace_bytes", "asa_bwd_workspace_bytes",
+              "asa_mask_seeded_workspace_bytes"):
         getattr(L, n).restype = ctypes.c_size_t
         getattr(L, n).argtypes = [pp]
     L.asa_build_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.asa_build_mask_seeded.argtypes = [pp, ctypes.c_uint64] + [vp] * 9 + [ctypes.c_size_t, vp]
+    L.asa_sample_offsets.argtypes = [pp, ctypes.c_uint64, vp, vp]
     L.asa_mask_from_scores.argtypes = [pp, vp, vp, vp]
     L.asa_csr_from_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -73,7 +77,7 @@ def load():
     L.asa_attn_bwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 17 + [ctypes.c_size_t, vp]
     for n in ("asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
               "asa_attn_bwd", "asa_set_kernel_timing", "asa_global_tokens", "asa_attn_fwd_g",
-              "asa_attn_bwd_g"):
+              "asa_attn_bwd_g", "asa_build_mask_seeded", "asa_sample_offsets"):
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -189,6 +193,24 @@ def asa_attn_bwd(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row
                                _ptr(d_o), _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
                                _ptr(row_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                ws_bytes, _stream(stream)), "asa_attn_bwd")
+
+
+def asa_mask_seeded_workspace_bytes(p: Params) -> int:
+    return int(load().asa_mask_seeded_workspace_bytes(ctypes.byref(p.c())))
+
+
+def asa_build_mask_seeded(p: Params, seed: int, q, k, mask, row_ptr, col_idx, col_ptr, row_idx,
+                          p_imp, workspace, stream=None):
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().asa_build_mask_seeded(ctypes.byref(p.c()), seed, _ptr(q), _ptr(k), _ptr(mask),
+                                        _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx),
+                                        _ptr(p_imp), _ptr(workspace), ws_bytes, _stream(stream)),
+           "asa_build_mask_seeded")
+
+
+def asa_sample_offsets(p: Params, seed: int, table, stream=None):
+    _check(load().asa_sample_offsets(ctypes.byref(p.c()), seed, _ptr(table), _stream(stream)),
+           "asa_sample_offsets")
 
 
 def asa_global_token_count(p: Params, n: int) -> int:

@@ -146,9 +146,14 @@ size_t asa_bwd_workspace_bytes(const asa_params *p) {
   return bwd_workspace_bytes(pb);
 }
 
-int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *mask,
-                   int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,
-                   float *p_imp, void *workspace, size_t workspace_bytes, void *hip_stream) {
+static size_t table_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.Nb * pb.ks);
+}
+
+static int build_mask_impl(const asa_params *p, const uint64_t *seed, const void *q, const void *k,
+                           uint8_t *mask, int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr,
+                           int32_t *row_idx, float *p_imp, void *workspace, size_t workspace_bytes,
+                           void *hip_stream) {
   Problem pb;
   int rc = resolve(p, &pb);
   if (rc != ASA_OK) return rc;
@@ -157,19 +162,54 @@ int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *m
   if (!aligned16(q) || !aligned16(k) || !aligned4(row_ptr) || !aligned4(col_idx) ||
       !aligned4(col_ptr) || !aligned4(row_idx) || !aligned4(p_imp))
     return ASA_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < asa_mask_workspace_bytes(p) || !aligned16(workspace))
+  const size_t base = asa_mask_workspace_bytes(p);
+  if (!workspace || workspace_bytes < base + (seed ? table_bytes(pb) : 0) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
-  float *scores = p_imp ? p_imp
-                        : reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(workspace) +
-                                                    probe_workspace_bytes(pb));
+  unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+  float *scores = p_imp ? p_imp : reinterpret_cast<float *>(ws + probe_workspace_bytes(pb));
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  uint8_t *table = nullptr;
+  if (seed) {
+    table = ws + base;
+    hipError_t e0 = launch_sample_offsets(pb, *seed, table, st);
+    if (e0 != hipSuccess) return finish(e0);
+  }
   timing_begin(st);
-  hipError_t e = launch_probe(pb, q, k, scores, workspace, st);
+  hipError_t e = launch_probe(pb, q, k, scores, workspace, st, table);
   timing_end(st);
   if (e != hipSuccess) return finish(e);
   e = launch_rule(pb, scores, mask, st);
   if (e != hipSuccess) return finish(e);
   return finish(launch_csr(pb, mask, row_ptr, col_idx, col_ptr, row_idx, st));
+}
+
+int asa_build_mask(const asa_params *p, const void *q, const void *k, uint8_t *mask,
+                   int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,
+                   float *p_imp, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return build_mask_impl(p, nullptr, q, k, mask, row_ptr, col_idx, col_ptr, row_idx, p_imp, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+size_t asa_mask_seeded_workspace_bytes(const asa_params *p) {
+  Problem pb;
+  if (resolve(p, &pb) != ASA_OK) return 0;
+  return asa_mask_workspace_bytes(p) + table_bytes(pb);
+}
+
+int asa_build_mask_seeded(const asa_params *p, uint64_t seed, const void *q, const void *k,
+                          uint8_t *mask, int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr,
+                          int32_t *row_idx, float *p_imp, void *workspace, size_t workspace_bytes,
+                          void *hip_stream) {
+  return build_mask_impl(p, &seed, q, k, mask, row_ptr, col_idx, col_ptr, row_idx, p_imp, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+int asa_sample_offsets(const asa_params *p, uint64_t seed, uint8_t *table, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (!table) return ASA_ERR_INVALID_ARG;
+  return finish(launch_sample_offsets(pb, seed, table, reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
 int asa_mask_from_scores(const asa_params *p, const float *scores, uint8_t *mask,

@@ -69,7 +69,8 @@ hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const voi
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
-                        void *rt_workspace, hipStream_t st);
+                        void *rt_workspace, hipStream_t st, const uint8_t *table = nullptr);
+hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st);
 size_t probe_workspace_bytes(const Problem &pb);
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);
 hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const void *v,

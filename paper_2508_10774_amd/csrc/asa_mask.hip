@@ -34,6 +34,7 @@ struct ProbeArgs {
   int n_valid_last;  // sampled tokens of the last block that lie below L
   float scale;
   int offs[kMaxSamples];
+  const uint8_t *table;   // per-block sample positions [slab][Nb][ks] (TAB kernels), else null
 };
 
 constexpr int kProbeQBlocks = 8;   // query blocks per workgroup
@@ -53,7 +54,9 @@ __device__ __forceinline__ int probe_swz(int row) {
   return D == 128 ? ((row & 7) | (((row >> 4) & 1) << 3)) : (((row >> 1) & 3) | (((row >> 4) & 1) << 2));
 }
 
-template <int D>
+// TAB: the sample positions differ from block to block and come from a table (seeded random
+// sampling) instead of one offset vector for all blocks.
+template <int D, bool TAB>
 __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
   constexpr int ROWS = kProbeKBlocks * 16;          // sampled rows per chunk
   constexpr int CH = D / 8;                         // 16-byte chunks per row
@@ -82,7 +85,20 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
   const bf16 *qs = slab_ptr(a.q, a.tq, slab, a.H);
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
 
-  auto offset_of = [&](int u) {
+  // TAB: this slab's table in LDS; positions ascend inside a block, so the samples of the last
+  // block that lie below L are a prefix
+  __shared__ uint8_t tab[TAB ? kMaxNb * kMaxSamples : 16];
+  int n_valid_last = a.n_valid_last;
+  if (TAB) {
+    const uint8_t *g = a.table + (int64_t)slab * a.Nb * a.ks;
+    for (int t = tid; t < a.Nb * a.ks; t += 512) tab[t] = g[t];
+    __syncthreads();
+    n_valid_last = 0;
+    for (int u = 0; u < a.ks; ++u)
+      if ((a.Nb - 1) * a.block + tab[(a.Nb - 1) * a.ks + u] < a.L) ++n_valid_last;
+  }
+  auto offset_of = [&](int blk, int u) {
+    if (TAB) return (blk < a.Nb && u < a.ks) ? (int)tab[blk * a.ks + u] : 0;
     int o = 0;
 #pragma unroll
     for (int x = 0; x < kMaxSamples; ++x)
@@ -90,7 +106,7 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
     return o;
   };
   auto valid_in_block = [&](int blk) {
-    return blk >= a.Nb ? 0 : (blk == a.Nb - 1 ? a.n_valid_last : a.ks);
+    return blk >= a.Nb ? 0 : (blk == a.Nb - 1 ? n_valid_last : a.ks);
   };
 
   // B operand: column n = sampled query (n & 15) of query block i0 + (n >> 4)
@@ -98,7 +114,7 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
   const bool q_ok = (n & 15) < valid_in_block(q_blk);
   bf16x8 qreg[D / 16];
   {
-    const int64_t qpos = q_ok ? (int64_t)q_blk * a.block + offset_of(n & 15) : 0;
+    const int64_t qpos = q_ok ? (int64_t)q_blk * a.block + offset_of(q_blk, n & 15) : 0;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + qpos * a.tq.sL + 16 * s + 8 * hl);
@@ -112,7 +128,7 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
   for (int i = 0; i < DMA_PER_WAVE; ++i) {
     const int seg = wave * DMA_PER_WAVE + i;
     const int row = seg * (64 / CH) + lane / CH;
-    dma_tok[i] = (row / 16) * a.block + offset_of(row % 16);
+    dma_tok[i] = (row / 16) * a.block + (TAB ? 0 : offset_of(0, row % 16));
     dma_pos[i] = ((lane % CH) ^ probe_swz<D>(row)) * 8;
   }
   auto fetch = [&](int chunk, int buf) __attribute__((always_inline)) {
@@ -120,6 +136,10 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
     for (int i = 0; i < DMA_PER_WAVE; ++i) {
       const int seg = wave * DMA_PER_WAVE + i;
       int64_t tok = (int64_t)chunk * kProbeKBlocks * a.block + dma_tok[i];
+      if (TAB) {
+        const int row = seg * (64 / CH) + lane / CH;
+        tok += offset_of(chunk * kProbeKBlocks + row / 16, row % 16);
+      }
       tok = tok < a.L ? tok : 0;   // padded samples: any valid row, masked out below
       probe_dma16(ks + tok * a.tk.sL + dma_pos[i], &Kc[buf][seg * 512]);
     }
@@ -237,8 +257,9 @@ size_t probe_workspace_bytes(const Problem &pb) {
 }
 
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
-                        void *rt_workspace, hipStream_t st) {
+                        void *rt_workspace, hipStream_t st, const uint8_t *table) {
   ProbeArgs a;
+  a.table = table;
   a.q = q; a.k = k; a.p_imp = p_imp; a.rt = reinterpret_cast<float *>(rt_workspace);
   a.tq = pb.q; a.tk = pb.k;
   a.H = pb.H; a.L = pb.L; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs; a.block = pb.block; a.ks = pb.ks;
@@ -252,16 +273,72 @@ hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *
   const int lds = 2 * kProbeKBlocks * 16 * pb.d * 2;   // two chunks of sampled key rows
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        2 * kProbeKBlocks * 16 * 128 * 2);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * kProbeKBlocks * 16 * 128 * 2);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
-  if (pb.d == 128)
-    hipLaunchKernelGGL(probe_kernel<128>, dim3(grid), dim3(512), lds, st, a);
+  if (pb.d == 128 && table)
+    hipLaunchKernelGGL((probe_kernel<128, true>), dim3(grid), dim3(512), lds, st, a);
+  else if (pb.d == 128)
+    hipLaunchKernelGGL((probe_kernel<128, false>), dim3(grid), dim3(512), lds, st, a);
+  else if (table)
+    hipLaunchKernelGGL((probe_kernel<64, true>), dim3(grid), dim3(512), lds, st, a);
   else
-    hipLaunchKernelGGL(probe_kernel<64>, dim3(grid), dim3(512), lds, st, a);
+    hipLaunchKernelGGL((probe_kernel<64, false>), dim3(grid), dim3(512), lds, st, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Seeded random sampling (Alg. 3 step 2 made reproducible).  Philox-4x32 with 10 rounds
+// (Salmon et al., SC'11) gives position j of block `blk` of slab `slab` the word
+// Philox(counter = (j, blk, slab, 0), key = seed)[0]; the k positions with the smallest
+// (word, j) are the block's sample, written in ascending position.  One wavefront per block.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                        uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+__global__ __launch_bounds__(64) void sample_offsets_kernel(uint32_t seed_lo, uint32_t seed_hi,
+                                                            int Nb, int b, int ks, uint8_t *table) {
+  __shared__ uint64_t word[128];   // (philox word, position): distinct, so ranks are too
+  __shared__ uint8_t chosen[128];
+  const int blk = blockIdx.x, slab = blockIdx.y, lane = threadIdx.x;
+  for (int j = lane; j < b; j += 64)
+    word[j] = ((uint64_t)philox4x32_10_word0((uint32_t)j, (uint32_t)blk, (uint32_t)slab, 0u, seed_lo, seed_hi) << 32) | (uint32_t)j;
+  __syncthreads();
+  for (int j = lane; j < b; j += 64) {
+    int rank = 0;
+    for (int x = 0; x < b; ++x) rank += word[x] < word[j];
+    chosen[j] = rank < ks;
+  }
+  __syncthreads();
+  if (lane == 0) {
+    uint8_t *out = table + ((int64_t)slab * Nb + blk) * ks;
+    int n = 0;
+    for (int j = 0; j < b; ++j)
+      if (chosen[j]) out[n++] = (uint8_t)j;
+  }
+}
+
+hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st) {
+  hipLaunchKernelGGL(sample_offsets_kernel, dim3(pb.Nb, pb.n_slabs), dim3(64), 0, st,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), pb.Nb, pb.block, pb.ks, table);
   return hipGetLastError();
 }
 
