@@ -135,16 +135,16 @@ struct FwdCfg {
 // The maximum is never allowed to lag behind: a row dominated by one key then has that key's
 // probability equal to exactly 1, free of bf16 rounding, which the backward's Delta relies on.
 //
-// PREFETCH = false: one LDS stage (32 KB at d = 128); the copies of a step are waited for right
-// away and the second workgroup on the CU computes meanwhile.  PREFETCH = true: two stages, the
-// next step's tiles are requested before the current step is computed.  Both were measured;
-// the single-stage form is the faster one on MI355X and is the one that is launched.
-template <int BLK, int D, bool PREFETCH>
+// Single-stage kernel: one workgroup per query block, all wavefronts in lock step, one LDS stage
+// (32 KB at d = 128); the copies of a step are waited for right away and the second workgroup
+// on the CU computes meanwhile.  (A two-stage variant that requested the next step's tiles
+// before computing the current one was measured and was slower.)  It serves tensors that the
+// ping-pong kernel below does not take (slabs of 4 GiB and more).
+template <int BLK, int D>
 __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
   using C = FwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
   bf16 *lds = reinterpret_cast<bf16 *>(smem);
-  constexpr int kStage = C::kKElems + C::kVElems;
   __shared__ int cols[kMaxNb];
 
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
@@ -191,28 +191,19 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_steps = n_tiles * C::kSub;
-  auto fetch = [&](int step, int stage) __attribute__((always_inline)) {
+  auto fetch = [&](int step) __attribute__((always_inline)) {
     const int j = cols[step / C::kSub];
     const int sub = step % C::kSub;
-    bf16 *Kd = lds + stage * kStage;
+    bf16 *Kd = lds;
     copy_k.issue(Kd, ks, j * BLK + sub * C::kKT, a.L);
     copy_v.issue(Kd + C::kKElems, vts + (int64_t)j * D * BLK, sub * C::kKT);
   };
-  __syncthreads();   // cols[] is complete
-  if (PREFETCH && n_steps > 0) fetch(0, 0);
   for (int step = 0; step < n_steps; ++step) {
-    const int stage = PREFETCH ? (step & 1) : 0;
-    if (PREFETCH) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // my copies of this step have landed
-      __syncthreads();                      // everyone's have; the other stage is free
-      if (step + 1 < n_steps) fetch(step + 1, stage ^ 1);
-    } else {
-      __syncthreads();
-      fetch(step, 0);
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-    }
-    const bf16 *Ks = lds + stage * kStage;
+    __syncthreads();                      // cols[] is complete; the stage is free again
+    fetch(step);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // my copies of this step have landed
+    __syncthreads();                      // everyone's have
+    const bf16 *Ks = lds;
     const bf16 *Vs = Ks + C::kKElems;
     const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kKT;
     f32x16 sacc[C::kKT / 32];
@@ -833,7 +824,7 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   constexpr int lds = (C::kKElems + C::kVElems) * 2;   // one stage
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D, false>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -856,7 +847,7 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
       hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, false>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((fwd_kernel<BLK, D, false>), dim3(grid), dim3(C::kThreads), lds, st, a);
+  hipLaunchKernelGGL((fwd_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), lds, st, a);
   return hipGetLastError();
 }
 
