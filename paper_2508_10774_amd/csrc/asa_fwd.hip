@@ -345,7 +345,7 @@ using Int = std::integral_constant<int, N>;
 
 // GT: with the pooled (global) tokens of ASA_G appended to every query block's list
 template <int BLK, int D, bool GT>
-__global__ __launch_bounds__(BLK * 4, 1) void fwd_pp_kernel(FwdArgs a) {
+__global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_pp_kernel(FwdArgs a) {   // (2: its LDS allows it)
   using C = PpCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
   bf16 *ldsK = reinterpret_cast<bf16 *>(smem);
@@ -830,12 +830,16 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
     attr_set = true;
   }
   int grid = xcd_grid(a.n_slabs * a.Nb);
-  // The ping-pong kernel addresses K tiles by 32-bit byte offsets inside a slab; tensors whose
-  // slabs span 4 GiB or more take the single-stage kernel.  (ASA_FWD_PLAIN=1 forces the latter:
-  // used to compare the two.)
+  // The ping-pong kernel is the faster one at block = 128, d = 128 (998 vs 914 TFLOP/s at the Wan
+  // shape); with smaller blocks or heads its workgroup has too few wavefronts per SIMD or too
+  // little work per phase and the single-stage kernel wins (e.g. 761 vs 511 TFLOP/s at block 64,
+  // d 128).  It addresses K tiles by 32-bit byte offsets inside a slab, so slabs of 4 GiB and
+  // more also take the single-stage kernel.  Global tokens exist in the ping-pong kernel only.
+  // ASA_FWD_PLAIN=1 / ASA_FWD_PINGPONG=1 force one or the other (used to compare and test them).
   const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
   if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb || a.tk.sL != D)) return hipErrorNotSupported;
-  if (fits32 && (a.Nbg > 0 || !getenv("ASA_FWD_PLAIN"))) {
+  const bool prefer_pp = (BLK == 128 && D == 128 && !getenv("ASA_FWD_PLAIN")) || getenv("ASA_FWD_PINGPONG");
+  if (fits32 && (a.Nbg > 0 || prefer_pp)) {
     using P = PpCfg<BLK, D>;
     const void *fn = a.Nbg > 0 ? reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, true>)
                                : reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, false>);

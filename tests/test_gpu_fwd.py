@@ -96,6 +96,14 @@ def test_fwd_single_stage_kernel_is_still_correct(monkeypatch):
     _check_fwd(p, qb, kb, vb, synth.random_block_mask(p.Nb, 0.6, seed=6, slabs=1))
 
 
+@pytest.mark.parametrize("L,d,block", [(1024, 64, 64), (520, 128, 64), (300, 64, 128)])
+def test_fwd_ping_pong_kernel_at_the_sizes_where_it_is_not_the_default(monkeypatch, L, d, block):
+    monkeypatch.setenv("ASA_FWD_PINGPONG", "1")
+    p = binding.Params(B=1, H=2, L=L, d=d, block=block)
+    qb, kb, vb = _case(1, 2, L, d, block, seed=L)
+    _check_fwd(p, qb, kb, vb, synth.random_block_mask(p.Nb, 0.5, seed=L, slabs=2))
+
+
 def test_fwd_tiny_workload_with_oracle_mask():
     w = synth.TINY
     qb, kb, vb = synth.make_qkv(w, seed=0)
