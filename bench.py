@@ -2,7 +2,7 @@
 """Benchmark of the ASA hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan|cog|wan-padded]
-                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref] [--no-asa-g]
+                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref] [--no-asa-g] [--no-gilbert]
 
 One step = one pass of the whole path over one batch of seeded synthetic video-token tensors
 that are already resident in HBM: mask generation (asa_build_mask), block-sparse forward
@@ -50,6 +50,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-ref", action="store_true")
     ap.add_argument("--no-asa-g", action="store_true")
+    ap.add_argument("--no-gilbert", action="store_true")
     ap.add_argument("--cpu-sample-slabs", type=int, default=12)
     return ap.parse_args()
 
@@ -170,6 +171,47 @@ def main():
                  "pool_ms": round(med(0), 4), "fwd_ms": round(med(1), 4), "bwd_ms": round(med(2), 4)}
         del ws_fg, ws_bg
 
+    # Gilbert-curve rearrangement (done once per video, outside the timed steps): host time of the
+    # order, the Q/K/V gather and the O scatter-back, and what it does to the density that the
+    # threshold rule picks when the retention bounds are left open
+    gil = None
+    if not args.no_gilbert:
+        t0 = time.perf_counter()
+        order, inverse = binding.asa_gilbert_order(*w.grid, w.n_text)
+        order_ms = (time.perf_counter() - t0) * 1e3
+        order_d, inverse_d = order.cuda(), inverse.cuda()
+        qg, kg_, vg_ = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        r_ev = [[ev() for _ in range(5)] for _ in range(5)]
+        for e5 in r_ev:
+            e5[0].record(stream)
+            binding.asa_set_kernel_timing(e5[1], e5[2])
+            binding.asa_reorder_tokens(p, [q, k, v], [qg, kg_, vg_], order_d)
+            e5[3].record(stream)
+            binding.asa_reorder_tokens(p, [o], [dq], inverse_d)
+            e5[4].record(stream)
+        torch.cuda.synchronize()
+        qkv_ms = float(np.median([e5[1].elapsed_time(e5[2]) for e5 in r_ev[1:]]))
+        o_ms = float(np.median([e5[3].elapsed_time(e5[4]) for e5 in r_ev[1:]]))
+        row_bytes = 2 * p.d * 2      # one read and one write of a bf16 row
+        qkv_bytes = 3 * p.B * p.H * p.L * row_bytes
+        p_open = binding.Params(B=w.B, H=w.H, L=w.L, d=w.d, block=w.block, k_samples=w.k_samples,
+                                tau=args.tau, r_min=0.0, r_max=1.0, n_prefix_dense=w.n_text)
+        bufs2 = binding.alloc_index_lists(p_open)
+        dens_open = []
+        for qq, kk in ((q, k), (qg, kg_)):
+            binding.asa_build_mask(p_open, qq, kk, bufs2["mask"], bufs2["row_ptr"], bufs2["col_idx"],
+                                   bufs2["col_ptr"], bufs2["row_idx"], None, ws_mask)
+            torch.cuda.synchronize()
+            dens_open.append(float(bufs2["row_ptr"][:, -1].to(torch.int64).sum().item())
+                             / (p.B * p.H * p.Nb * p.Nb))
+        gil = {"order_host_ms": round(order_ms, 2), "reorder_qkv_ms": round(qkv_ms, 4),
+               "reorder_qkv_gbs": round(qkv_bytes / (qkv_ms * 1e-3) / 1e9, 1),
+               "reorder_qkv_frac_of_hbm_peak": round(qkv_bytes / (qkv_ms * 1e-3) / 8e12, 4),
+               "reorder_o_ms": round(o_ms, 4),
+               "density_at_tau_raster_order": round(dens_open[0], 5),
+               "density_at_tau_gilbert_order": round(dens_open[1], 5)}
+        del qg, kg_, vg_, bufs2
+
     mask_ms = np.array([e["s0"].elapsed_time(e["s1"]) for e in per_step])
     fwd_ms = np.array([e["s1"].elapsed_time(e["s2"]) for e in per_step])
     bwd_ms = np.array([e["s2"].elapsed_time(e["s3"]) for e in per_step])
@@ -224,8 +266,10 @@ def main():
         "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
         "asa_g": asa_g,
+        "gilbert": gil,
         "roofline": {
-            "kernel": f"fwd_pp_kernel<{p.block},{p.d}>",
+            "kernel": (f"fwd_pp_kernel<{p.block},{p.d}>" if (p.block, p.d) == (128, 128)
+                       else f"fwd_kernel<{p.block},{p.d}>"),
             "bound": "mfma",
             "achieved": round(float(kern_tflops), 2),
             "peak": PEAK_BF16_TFLOPS,

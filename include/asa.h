@@ -210,8 +210,36 @@ int asa_attn_bwd_g(const asa_params *p, int n, const void *q, const void *k, con
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Token rearrangement along a Gilbert (generalised Hilbert) curve (Sec. 3.3 "Preprocessing and
+ * Importance Estimation"; Alg. 3 step 1): before the sequence is cut into blocks, the tokens of
+ * the T x Y x X video grid are put into the order in which a space-filling curve visits them, so
+ * that a block holds tokens that are neighbours in the video.  The paper names the curve and does
+ * not define it; this library's curve visits every cell once, moves one cell along one axis per
+ * step for every grid (its major axis is the longest axis of even length, the longest axis if
+ * all are odd), and is the classical Hilbert curve on a 2^k square.
+ *
+ * asa_gilbert_order -- HOST function, no GPU work.  order, inverse: HOST arrays of
+ * n_prefix + T*Y*X int32 (inverse may be NULL).  Position i of the rearranged sequence holds the
+ * token that raster order (t major, then y, then x; after n_prefix leading tokens, which keep
+ * their places) holds at order[i]; inverse[order[i]] = i.  At most 2^30 tokens.
+ *
+ * asa_reorder_tokens -- dst[t][b, h, i, :] = src[t][b, h, index[i], :] for t < n_tensors <= 3
+ * tensors [B, H, L, d] bf16 in one launch (Q, K, V with index = order before the attention
+ * calls; O, dQ, dK, dV with index = inverse after them).  index: DEVICE [L] int32; an entry
+ * outside [0, L) gives a zero row.  src, dst: HOST arrays of n_tensors device pointers, read
+ * during the call; a tensor cannot be its own destination.  src_stride / dst_stride: element
+ * strides {B, H, L} of all sources / all destinations, NULL = packed (the strides in `p` are not
+ * used).  Of `p` only B, H, L, d have a meaning here.
+ */
+int asa_gilbert_order(int32_t T, int32_t Y, int32_t X, int32_t n_prefix, int32_t *order,
+                      int32_t *inverse);
+int asa_reorder_tokens(const asa_params *p, int32_t n_tensors, const void *const *src,
+                       void *const *dst, const int64_t *src_stride, const int64_t *dst_stride,
+                       const int32_t *index, void *hip_stream);
+
+/*
  * Profiling hook for benchmarks.  Arms the calling thread so that the NEXT asa_attn_fwd,
- * asa_attn_bwd or asa_build_mask call records `start_event` immediately before and
+ * asa_attn_bwd, asa_build_mask or asa_reorder_tokens call records `start_event` immediately before and
  * `stop_event` immediately after its dominant kernel(s) -- the tile loop of the forward, the
  * dK/dV and dQ kernels of the backward, the probe of the mask build -- on the call's stream,
  * leaving out the small preparation kernels around them.  Both are hipEvent_t handles owned by

@@ -41,7 +41,7 @@ EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_wo
            "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
            "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
            "asa_attn_bwd_g", "asa_mask_seeded_workspace_bytes", "asa_build_mask_seeded",
-           "asa_sample_offsets"]
+           "asa_sample_offsets", "asa_gilbert_order", "asa_reorder_tokens"]
 
 
 def load():
@@ -75,7 +75,9 @@ def load():
     L.asa_global_tokens.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp]
     L.asa_attn_fwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 11 + [ctypes.c_size_t, vp]
     L.asa_attn_bwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 17 + [ctypes.c_size_t, vp]
-    for n in ("asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
+    L.asa_gilbert_order.argtypes = [ctypes.c_int32] * 4 + [vp, vp]
+    L.asa_reorder_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
+    for n in ("asa_gilbert_order", "asa_reorder_tokens", "asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
               "asa_attn_bwd", "asa_set_kernel_timing", "asa_global_tokens", "asa_attn_fwd_g",
               "asa_attn_bwd_g", "asa_build_mask_seeded", "asa_sample_offsets"):
         getattr(L, n).restype = ctypes.c_int
@@ -247,6 +249,29 @@ def asa_attn_bwd_g(p: Params, n: int, q, k, v, kg, vg, o, d_o, lse, row_ptr, col
                                  _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx), _ptr(dq), _ptr(dk),
                                  _ptr(dv), _ptr(workspace), ws_bytes, _stream(stream)),
            "asa_attn_bwd_g")
+
+
+def asa_gilbert_order(T: int, Y: int, X: int, n_prefix: int = 0):
+    """(order, inverse) as int32 CPU tensors of n_prefix + T*Y*X entries (host function)."""
+    n = max(0, n_prefix) + max(0, T) * max(0, Y) * max(0, X)
+    order = torch.empty(n, dtype=torch.int32)
+    inverse = torch.empty(n, dtype=torch.int32)
+    _check(load().asa_gilbert_order(T, Y, X, n_prefix, ctypes.c_void_p(order.data_ptr()),
+                                    ctypes.c_void_p(inverse.data_ptr())), "asa_gilbert_order")
+    return order, inverse
+
+
+def asa_reorder_tokens(p: Params, src, dst, index, src_stride=None, dst_stride=None, stream=None):
+    """dst[t][b, h, i, :] = src[t][b, h, index[i], :] for lists of up to three tensors."""
+    n = len(src)
+    if len(dst) != n:
+        raise AsaError("asa_reorder_tokens: src and dst differ in length")
+    srcs = (ctypes.c_void_p * n)(*[t.data_ptr() for t in src])
+    dsts = (ctypes.c_void_p * n)(*[t.data_ptr() for t in dst])
+    ss = (ctypes.c_int64 * 3)(*src_stride) if src_stride is not None else None
+    ds = (ctypes.c_int64 * 3)(*dst_stride) if dst_stride is not None else None
+    _check(load().asa_reorder_tokens(ctypes.byref(p.c()), n, srcs, dsts, ss, ds, _ptr(index),
+                                     _stream(stream)), "asa_reorder_tokens")
 
 
 def asa_set_kernel_timing(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):

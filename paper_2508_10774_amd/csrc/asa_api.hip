@@ -408,4 +408,31 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
                            dv, workspace, reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
+int asa_gilbert_order(int32_t T, int32_t Y, int32_t X, int32_t n_prefix, int32_t *order,
+                      int32_t *inverse) {
+  if (!order || T < 1 || Y < 1 || X < 1 || n_prefix < 0) return ASA_ERR_INVALID_ARG;
+  if ((int64_t)T * Y * X + n_prefix > ((int64_t)1 << 30)) return ASA_ERR_UNSUPPORTED;
+  return gilbert_order(T, Y, X, n_prefix, order, inverse);
+}
+
+int asa_reorder_tokens(const asa_params *p, int32_t n_tensors, const void *const *src,
+                       void *const *dst, const int64_t *src_stride, const int64_t *dst_stride,
+                       const int32_t *index, void *hip_stream) {
+  Problem pb;
+  int rc = resolve(p, &pb);
+  if (rc != ASA_OK) return rc;
+  if (n_tensors < 1 || n_tensors > 3 || !src || !dst || !index || !aligned4(index)) return ASA_ERR_INVALID_ARG;
+  for (int t = 0; t < n_tensors; ++t) {
+    if (!src[t] || !dst[t] || !aligned16(src[t]) || !aligned16(dst[t])) return ASA_ERR_INVALID_ARG;
+    if (src[t] == dst[t]) return ASA_ERR_INVALID_ARG;  // not an in-place operation
+  }
+  const int64_t packed[3] = {0, 0, 0};
+  TensorView ts, td;
+  if (!view_from(src_stride ? src_stride : packed, pb, &ts) ||
+      !view_from(dst_stride ? dst_stride : packed, pb, &td))
+    return ASA_ERR_INVALID_ARG;
+  return finish(launch_reorder(pb, n_tensors, src, dst, ts, td, index,
+                               reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

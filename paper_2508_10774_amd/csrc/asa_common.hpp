@@ -70,6 +70,10 @@ hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, 
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
                         void *rt_workspace, hipStream_t st, const uint8_t *table = nullptr);
+int gilbert_order(int T, int Y, int X, int n_prefix, int32_t *order, int32_t *inverse);  // asa_status; host
+hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *src, void *const *dst,
+                          const TensorView &ts, const TensorView &td, const int32_t *index,
+                          hipStream_t st);
 hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st);
 size_t probe_workspace_bytes(const Problem &pb);
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);
