@@ -343,12 +343,15 @@ hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *tabl
 }
 
 // ---------------------------------------------------------------------------------------
-// Threshold rule (Alg. 3 steps 6-11), one workgroup per row of the importance map.
+// Threshold rule (Alg. 3 steps 6-11), one wavefront per row of the importance map.
 // The row is sorted by (score descending, block index ascending) with a bitonic network on
 // 64-bit keys (inverted order-preserving image of the fp32 score in the high word, the block
-// index in the low word).  One lane then forms the fp64 running sums c_r in rank order -- the
-// additions happen in exactly the sequence the algorithm states, so the decision is
-// bit-identical to a sequential implementation -- then m* = #{r : c_r < tau * T},
+// index in the low word).  The keys live in registers, NPAD / 64 consecutive ranks per lane:
+// network stages whose partners sit in the same lane are register compare-exchanges, the others
+// fetch the partner lane's key through the cross-lane network (no LDS memory traffic: with the
+// keys in LDS the kernel was bound by LDS bandwidth).  One lane then forms the fp64 running sums
+// c_r in rank order -- the additions happen in exactly the sequence the algorithm states, so the
+// decision is bit-identical to a sequential implementation -- then m* = #{r : c_r < tau * T},
 // m = clamp(m*, m_min, m_max), keep rank < m.  A NaN score counts as 0.
 // ---------------------------------------------------------------------------------------
 struct RuleArgs {
@@ -370,43 +373,66 @@ __device__ __forceinline__ float key_score(uint32_t k) {
   return __uint_as_float(u);
 }
 
-// One wavefront per row (4 rows per workgroup): every step below is wave-synchronous, so the
-// sorting network needs no workgroup barriers, and the sequential running sums of different
-// rows run on different SIMDs.
+// Four rows per workgroup, one per wavefront: every step below is wave-synchronous, so there
+// are no workgroup barriers, and the sequential running sums of different rows run on
+// different SIMDs.
 template <int NPAD>
 __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
-  __shared__ unsigned long long keys_all[4][NPAD];
+  constexpr int E = NPAD / 64;               // keys per lane; rank of key r of a lane = lane * E + r
   __shared__ double cum_all[4][NPAD];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + wave;          // slab * Nb + i
   if (row >= a.n_rows) return;                     // whole wavefront; no workgroup barriers below
-  unsigned long long *keys = keys_all[wave];
   double *cum = cum_all[wave];
   const int i = row % a.Nb;
   const float *src = a.scores + (int64_t)row * a.Nb;
-  for (int j = lane; j < NPAD; j += 64)
-    keys[j] = j < a.Nb ? (((unsigned long long)desc_key(src[j]) << 32) | (unsigned)j)
-                       : ~0ull;        // padding sorts last
-  __builtin_amdgcn_wave_barrier();
-  for (int k = 2; k <= NPAD; k <<= 1)
-    for (int jj = k >> 1; jj > 0; jj >>= 1) {
+  unsigned long long key[E];
 #pragma unroll
-      for (int t0 = 0; t0 < NPAD / 2; t0 += 64) {
-        const int t = t0 + lane;
-        const int lo = ((t & ~(jj - 1)) << 1) | (t & (jj - 1));
-        const int hi = lo + jj;
-        const unsigned long long x = keys[lo], y = keys[hi];
-        const bool up = (lo & k) == 0;
-        if ((x > y) == up) {
-          keys[lo] = y;
-          keys[hi] = x;
+  for (int r = 0; r < E; ++r) {
+    const int j = lane * E + r;
+    key[r] = j < a.Nb ? (((unsigned long long)desc_key(src[j]) << 32) | (unsigned)j)
+                      : ~0ull;        // padding sorts last
+  }
+  // ascending bitonic network over e = lane * E + r: stage (k, jj) orders the pair (e, e ^ jj)
+  // upwards where (e & k) == 0 and downwards elsewhere
+  for (int k = 2; k <= NPAD; k <<= 1) {
+    // partners in other lanes: lane ^ (jj / E), same register
+    for (int jj = k >> 1; jj >= E; jj >>= 1) {
+      const int dl = jj / E;
+      const bool up = ((lane * E) & k) == 0;           // (k > jj >= E: decided by the lane)
+      const bool keep_min = ((lane & dl) == 0) == up;
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const uint32_t lo = (uint32_t)key[r], hi = (uint32_t)(key[r] >> 32);
+        const unsigned long long other =
+            ((unsigned long long)(uint32_t)__shfl_xor((int)hi, dl, 64) << 32) | (uint32_t)__shfl_xor((int)lo, dl, 64);
+        const bool other_smaller = other < key[r];
+        key[r] = (other_smaller == keep_min) ? other : key[r];
+      }
+    }
+    // partners in the same lane: registers r and r ^ jj
+#pragma unroll
+    for (int jj = E >> 1; jj > 0; jj >>= 1) {
+      if (jj < k) {
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+          if ((r & jj) == 0) {
+            const bool up = ((lane * E + r) & k) == 0;
+            const unsigned long long x = key[r], y = key[r ^ jj];
+            const bool swap = (x > y) == up;
+            key[r] = swap ? y : x;
+            key[r ^ jj] = swap ? x : y;
+          }
         }
       }
-      __builtin_amdgcn_wave_barrier();
     }
-  // scores in rank order as fp64 (in parallel), zero-padded
-  for (int r = lane; r < NPAD; r += 64)
-    cum[r] = r < a.Nb ? (double)key_score((uint32_t)(keys[r] >> 32)) : 0.0;
+  }
+  // scores in rank order as fp64, zero-padded
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int e = lane * E + r;
+    cum[e] = e < a.Nb ? (double)key_score((uint32_t)(key[r] >> 32)) : 0.0;
+  }
   __builtin_amdgcn_wave_barrier();
   // Running sums in place: cum[r] becomes c_{r+1} = sum of the r+1 best scores.  Sequential on
   // purpose (see above): one lane, eight values fetched at a time so that only the additions
@@ -429,16 +455,24 @@ __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
   __builtin_amdgcn_wave_barrier();
   const double thr = (double)a.tau * cum[a.Nb - 1];   // tau * T
   int inside = 0;
-  for (int r = lane; r < a.Nb; r += 64) inside += ((r == 0 ? 0.0 : cum[r - 1]) < thr);
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int e = lane * E + r;
+    if (e < a.Nb) inside += ((e == 0 ? 0.0 : cum[e - 1]) < thr);
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) inside += __shfl_xor(inside, off, 64);
   int m = inside;
   m = m < a.m_min ? a.m_min : m;
   m = m > a.m_max ? a.m_max : m;
   uint8_t *dst = a.mask + (int64_t)row * a.Nb;
-  for (int r = lane; r < a.Nb; r += 64) {
-    const int j = (int)(keys[r] & 0xffffffffu);
-    dst[j] = (r < m) || (i < a.n_prefix_blocks) || (j < a.n_prefix_blocks);
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int e = lane * E + r;
+    if (e < a.Nb) {
+      const int j = (int)(key[r] & 0xffffffffu);
+      dst[j] = (e < m) || (i < a.n_prefix_blocks) || (j < a.n_prefix_blocks);
+    }
   }
 }
 
