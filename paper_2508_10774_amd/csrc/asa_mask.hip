@@ -1,6 +1,8 @@
 // Mask generation for gfx950: block importance map (Alg. 2 -> Alg. 1 of the paper's appendix),
 // the threshold rule (Alg. 3 steps 6-11) and the CSR / CSC index lists that drive the
 // block-sparse attention kernels.
+#include <type_traits>
+
 #include "asa_common.hpp"
 
 namespace asa {
@@ -57,7 +59,7 @@ __device__ __forceinline__ int probe_swz(int row) {
 // TAB: the sample positions differ from block to block and come from a table (seeded random
 // sampling) instead of one offset vector for all blocks.
 template <int D, bool TAB>
-__global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
+__global__ __launch_bounds__(512, 4) void probe_kernel(ProbeArgs a) {   // (4 wavefronts per SIMD: two workgroups per CU)
   constexpr int ROWS = kProbeKBlocks * 16;          // sampled rows per chunk
   constexpr int CH = D / 8;                         // 16-byte chunks per row
   constexpr int DMA_PER_WAVE = ROWS * CH / 64 / 8;  // 1 KB per wave instruction, 8 wavefronts
@@ -145,31 +147,58 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
     }
   };
 
+  // The common case of that, with all address arithmetic taken out of the sweep: one offset
+  // vector for all blocks and a chunk that lies wholly below L.  Per lane a byte offset inside
+  // the chunk, per chunk one wave-uniform base.
+  uint32_t dma_off0[DMA_PER_WAVE];   // bytes from the first token of the chunk
+#pragma unroll
+  for (int i = 0; i < DMA_PER_WAVE; ++i)
+    dma_off0[i] = (uint32_t)(((int64_t)dma_tok[i] * a.tk.sL + dma_pos[i]) * 2);
+  const int64_t chunk_stride = (int64_t)kProbeKBlocks * a.block * a.tk.sL * 2;   // bytes
+  // chunks with no token >= L (none if a chunk's rows span 4 GiB or more: 32-bit offsets)
+  const int n_full_chunks = (TAB || chunk_stride >= ((int64_t)1 << 32)) ? 0 : a.L / (kProbeKBlocks * a.block);
+  auto fetch_any = [&](int chunk, int buf) __attribute__((always_inline)) {
+    if (chunk < n_full_chunks) {
+      const char *base = reinterpret_cast<const char *>(ks) + chunk * chunk_stride;   // wave-uniform
+#pragma unroll
+      for (int i = 0; i < DMA_PER_WAVE; ++i)
+        probe_dma16(base + dma_off0[i], &Kc[buf][(wave * DMA_PER_WAVE + i) * 512]);
+    } else {
+      fetch(chunk, buf);
+    }
+  };
+
   // consumer: A row r = 8g + 4h + j is sample 4g + j of key block j0 + h
   const int a_row = ((n >> 2) & 1) * 16 + 4 * (n >> 3) + (n & 3);   // row inside a pair of key blocks
   const int a_swz = probe_swz<D>(a_row);
+  // my fragment s of the first pair of key blocks of my half of a chunk (elements from the
+  // start of the buffer); the second pair and the other buffer are constant distances away
+  int a_off[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s)
+    a_off[s] = (half * (kProbeKBlocks / 4) * 32 + a_row) * D + (((2 * s + hl) ^ a_swz) * 8);
+  // where my block-row maxima of chunk 0 go (floats from the start of rt)
+  const int rt_off = (2 * half * (kProbeKBlocks / 4) + hl) * 32 + n;
 
+  float rt_pend[kProbeKBlocks / 4];   // block-row maxima of the chunk just swept
   float Mt = -INFINITY;  // running maximum of my query over the key blocks of parity hl
   double lt = 0.0;       // running denominator over the same keys
+  const float c2 = a.scale * 1.44269504088896340736f;
 
-  const int n_chunks = nb_pad / kProbeKBlocks;
-  fetch(0, 0);
-  for (int chunk = 0; chunk < n_chunks; ++chunk) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): my loads of this chunk have landed
-    __syncthreads();                     // everyone's have, and the other buffer is free
-    if (chunk + 1 < n_chunks) fetch(chunk + 1, (chunk + 1) & 1);
-    const bf16 *Kb = Kc[chunk & 1];
+  // one chunk out of LDS buffer BUF (a compile-time constant: every LDS address of the sweep is
+  // a per-lane register plus an immediate)
+  auto sweep_chunk = [&](int chunk, auto buf_tag) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const bf16 *Kb = Kc[BUF];
 #pragma unroll
     for (int sb = 0; sb < kProbeKBlocks / 4; ++sb) {
-      const int sub = half * (kProbeKBlocks / 4) + sb;
-      const int j0 = chunk * kProbeKBlocks + 2 * sub;
-      const bf16 *rp = Kb + (sub * 32 + a_row) * D;
+      const int j0 = chunk * kProbeKBlocks + 2 * (half * (kProbeKBlocks / 4) + sb);
       f32x16 acc;
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * s + hl) ^ a_swz) * 8));
+        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(Kb + sb * 32 * D + a_off[s]);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc, 0, 0, 0);
       }
       // register i of lane half hl is sample i of key block j0 + hl; samples past L (only in
@@ -184,20 +213,51 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) mraw = fmaxf(mraw, acc[i]);
       const float mij = mraw * a.scale;                  // block-row maximum, Alg. 1 step 12
-      rt[(j0 + hl) * 32 + n] = mij;
+      rt_pend[sb] = mij;
       // Alg. 1 steps 12-15: tile-local exponentials exp(scale * (s - max)) as one fused
       // multiply-add and one exp2 each, then fold into the running pair
-      const float c2 = a.scale * 1.44269504088896340736f;
       const float bias = (mraw == -INFINITY) ? 0.f : -mraw * c2;
       float lij = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i) lij += fast_exp2(fmaf(acc[i], c2, bias));
-      const float mnew = fmaxf(Mt, mij);
-      const float mnew_s = (mnew == -INFINITY) ? 0.f : mnew;
-      lt = (double)__expf(Mt - mnew_s) * lt + (double)__expf(mij - mnew_s) * (double)lij;
-      Mt = mnew;
+      if (__any(mij > Mt)) {
+        const float mnew = fmaxf(Mt, mij);
+        const float mnew_s = (mnew == -INFINITY) ? 0.f : mnew;
+        lt = (double)__expf(Mt - mnew_s) * lt + (double)__expf(mij - mnew_s) * (double)lij;
+        Mt = mnew;
+      } else {
+        // no row's maximum grew (the usual case once the sweep has passed the query's own
+        // neighbourhood): the general update with a factor of exactly 1 on the old sum
+        lt += (double)__expf(mij - ((Mt == -INFINITY) ? 0.f : Mt)) * (double)lij;
+      }
     }
+  };
+
+  // The block-row maxima of a chunk are stored at the start of the NEXT chunk's turn, just before
+  // its loads are requested: the wait for those loads at the top of the turn after that also
+  // waits for the stores (one counter), and a store issued in the middle of a turn was not yet
+  // acknowledged at its end.
+  auto store_rt = [&](int chunk) __attribute__((always_inline)) {
+    float *rt_c = rt + (int64_t)chunk * kProbeKBlocks * 32;
+#pragma unroll
+    for (int sb = 0; sb < kProbeKBlocks / 4; ++sb) rt_c[rt_off + sb * 64] = rt_pend[sb];
+  };
+  const int n_chunks = nb_pad / kProbeKBlocks;
+  fetch_any(0, 0);
+  for (int chunk = 0; chunk < n_chunks; chunk += 2) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): my loads of this chunk have landed
+    __syncthreads();                     // everyone's have, and the other buffer is free
+    if (chunk > 0) store_rt(chunk - 1);
+    if (chunk + 1 < n_chunks) fetch_any(chunk + 1, 1);
+    sweep_chunk(chunk, std::integral_constant<int, 0>{});
+    if (chunk + 1 >= n_chunks) break;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    store_rt(chunk);
+    if (chunk + 2 < n_chunks) fetch_any(chunk + 2, 0);
+    sweep_chunk(chunk + 1, std::integral_constant<int, 1>{});
   }
+  store_rt(n_chunks - 1);
   // merge the two parities of each query
   {
     const float Mo = __shfl_xor(Mt, 32, 64);
@@ -216,19 +276,21 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
   {
     const int i = i_base + wave;
     if (i >= a.Nb) return;
+
     const int pr_ = wave >> 1, qb = wave & 1;           // its pair and position in the pair
     const float *rtq = a.rt + ((int64_t)work * 4 + pr_) * nb_pad * 32 + qb * 16;
     // merge the two wavefronts of the pair
-    float Mrow[16];
-    double Lrow[16];
+    // (the denominator is summed in fp64; its reciprocal is rounded to fp32 once per sampled
+    // row: the exponentials below are fp32 anyway)
+    float Mrow[16], Linv[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
       const float m0 = sM[pr_][qb * 16 + u], m1 = sM[pr_ + 4][qb * 16 + u];
       const float mm = fmaxf(m0, m1);
       const float ms = (mm == -INFINITY) ? 0.f : mm;
       Mrow[u] = mm;
-      Lrow[u] = (double)__expf(m0 - ms) * sL[pr_][qb * 16 + u] +
-                (double)__expf(m1 - ms) * sL[pr_ + 4][qb * 16 + u];
+      Linv[u] = (float)(1.0 / ((double)__expf(m0 - ms) * sL[pr_][qb * 16 + u] +
+                               (double)__expf(m1 - ms) * sL[pr_ + 4][qb * 16 + u]));
     }
     const int rows_ok = valid_in_block(i);
     float *out = a.p_imp + ((int64_t)slab * a.Nb + i) * a.Nb;
@@ -240,10 +302,7 @@ __global__ __launch_bounds__(512, 2) void probe_kernel(ProbeArgs a) {
       float best = 0.f;
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
-        if (u < rows_ok && rv[u] != -INFINITY) {
-          float pr = (float)((double)__expf(rv[u] - Mrow[u]) / Lrow[u]);
-          best = fmaxf(best, pr);
-        }
+        if (u < rows_ok && rv[u] != -INFINITY) best = fmaxf(best, __expf(rv[u] - Mrow[u]) * Linv[u]);
       }
       out[j] = best;
     }
