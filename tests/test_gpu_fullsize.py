@@ -195,3 +195,44 @@ def test_wan_global_tokens_forward_sampled_blocks(wan):
         e = util.assert_close_bf16(util.host_f32(o[0, h])[rows], want[rows], f"wan ASA_G O head {h}")
         assert np.abs(lse[h].cpu().numpy()[rows] - wl[rows]).max() <= util.LSE_ABS
         print(f"[fullsize] wan ASA_G O head {h}: scaled max {e[0]:.2e} mean {e[1]:.2e}", flush=True)
+
+
+def test_maximum_block_count_mask_forward_backward():
+    """Nb = 1024, the largest block count the library takes (L = 131 065 at block 128, ragged last
+    block): every per-block table is full.  Mask against the oracle on every row, forward and
+    backward on sampled blocks."""
+    Nb, block, d = 1024, 128, 128
+    L = Nb * block - 7
+    p = binding.Params(B=1, H=1, L=L, d=d, block=block, tau=0.9, r_min=0.0, r_max=0.02)
+    assert p.Nb == Nb
+    shape = (1, 1, L, d)
+    qb, kb, vb, gb = (synth.make_iid(shape, 2024, s) for s in range(4))
+    q, k, v, g = (util.dev_bf16(x) for x in (qb, kb, vb, gb))
+    bufs = binding.alloc_index_lists(p)
+    ws = binding.alloc_workspace(binding.asa_mask_workspace_bytes(p))
+    binding.asa_build_mask(p, q, k, bufs["mask"], bufs["row_ptr"], bufs["col_idx"], bufs["col_ptr"],
+                           bufs["row_idx"], None, ws)
+    torch.cuda.synchronize()
+    mask_g = bufs["mask"].cpu().numpy().reshape(Nb, Nb)
+    assert (mask_g.sum(axis=1) == 20).all()            # floor(0.02 * 1024): the clamp decides
+    qf, kf, vf, gf = (synth.bf16_bits_to_f32(x)[0, 0] for x in (qb, kb, vb, gb))
+    offs = synth.default_sample_offsets(block, 16)
+    mask_o, P = oracle.build_mask(qf[None, None], kf[None, None], block, offs, 0.9, 0.0, 0.02)
+    exact, excused, failed = util.classify_mask_rows(P, mask_o, mask_g[None, None], 0.9)
+    print(f"[fullsize] Nb=1024 mask rows: {exact} exact, {excused} excused", flush=True)
+    assert not failed, failed
+
+    o, lse, o_lo = util.run_fwd(p, q, k, v, bufs, with_lo=True)
+    dq, dk, dv = util.run_bwd(p, q, k, v, o, lse, g, bufs, o_lo=o_lo)
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    qblocks, kblocks = [0, 511, Nb - 1], [1, Nb - 1]
+    want, wl = oracle.attn_fwd(qf, kf, vf, mask_g, block, None, qblocks)
+    rows = ~np.isnan(wl)
+    util.assert_close_bf16(util.host_f32(o)[0, 0][rows], want[rows], "O")
+    assert np.abs(lse.cpu().numpy()[0][rows] - wl[rows]).max() <= util.LSE_ABS
+    wq, wk, wv = oracle.attn_bwd(qf, kf, vf, gf, mask_g, block, None, qblocks, kblocks)
+    rq, rk = ~np.isnan(wq[:, 0]), ~np.isnan(wk[:, 0])
+    util.assert_close_bf16(util.host_f32(dq)[0, 0][rq], wq[rq], "dQ")
+    util.assert_close_bf16(util.host_f32(dk)[0, 0][rk], wk[rk], "dK")
+    util.assert_close_bf16(util.host_f32(dv)[0, 0][rk], wv[rk], "dV")
