@@ -713,9 +713,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   auto run_group = [&](auto g_tag) __attribute__((always_inline)) {
     constexpr int G = decltype(g_tag)::value;
     using R0 = Int<G>;
-    using R1 = Int<(G + 1) & 3>;
     using R2 = Int<(G + 2) & 3>;
-    using R3 = Int<(G + 3) & 3>;
     int p = 0;
     if (G == 1) { phase_sync(p); dma_idle(Int<0>{}, false); ++p; }   // group 0's matrix slot
     const int n_own = n_steps > G ? (n_steps - G + 1) / 2 : 0;
