@@ -39,6 +39,21 @@ def test_workload_and_odd_shaped_grids_match_the_oracle(grid, n_prefix):
     assert np.array_equal(got_inv, want_inv)
 
 
+def test_random_grids_match_the_oracle_and_step_by_one_cell():
+    rng = np.random.default_rng(20250811)
+    for _ in range(60):
+        grid = tuple(int(x) for x in rng.integers(1, 41, size=3))
+        n_prefix = int(rng.integers(0, 4))
+        want, want_inv = gilbert.token_order(grid, n_prefix)
+        got, got_inv = _lib_order(grid, n_prefix)
+        assert np.array_equal(got, want), grid
+        assert np.array_equal(got_inv, want_inv), grid
+        r = got[n_prefix:].astype(np.int64) - n_prefix
+        cells = np.stack([r // (grid[1] * grid[2]), (r // grid[2]) % grid[1], r % grid[2]], axis=1)
+        if len(cells) > 1:
+            assert (np.abs(np.diff(cells, axis=0)).sum(axis=1) == 1).all(), grid
+
+
 def test_argument_checks():
     import ctypes
     L = binding.load()

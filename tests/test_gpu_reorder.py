@@ -56,6 +56,21 @@ def test_reorder_strided_source_and_bad_index_entries():
     assert np.array_equal(got, want)
 
 
+def test_reorder_three_tensors_into_a_strided_destination():
+    B, H, L, d = 1, 3, 777, 64
+    p = binding.Params(B=B, H=H, L=L, d=d, block=64)
+    bits = [synth.make_iid((B, H, L, d), seed=21, stream=t) for t in range(3)]
+    src = [util.dev_bf16(b) for b in bits]
+    # destination laid out [B, L, H, d]
+    dst = [torch.full((B, L, H, d), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    idx = np.random.default_rng(5).permutation(L).astype(np.int32)
+    binding.asa_reorder_tokens(p, src, dst, torch.from_numpy(idx).cuda(), dst_stride=(L * H * d, d, H * d))
+    torch.cuda.synchronize()
+    for t in range(3):
+        got = dst[t].permute(0, 2, 1, 3).contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, bits[t][:, :, idx, :]), t
+
+
 def test_reorder_rejects_bad_arguments():
     p = binding.Params(B=1, H=1, L=64, d=64, block=64)
     x = torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device="cuda")
