@@ -2,7 +2,7 @@
 """Benchmark of the ASA hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan|cog|wan-padded]
-                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref] [--no-asa-g] [--no-gilbert]
+                    [--density 0.25] [--no-bwd] [--no-cpu-baseline] [--no-dense-ref] [--no-asa-g] [--no-gilbert] [--no-sweep]
 
 One step = one pass of the whole path over one batch of seeded synthetic video-token tensors
 that are already resident in HBM: mask generation (asa_build_mask), block-sparse forward
@@ -51,6 +51,7 @@ def parse():
     ap.add_argument("--no-dense-ref", action="store_true")
     ap.add_argument("--no-asa-g", action="store_true")
     ap.add_argument("--no-gilbert", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--cpu-sample-slabs", type=int, default=12)
     return ap.parse_args()
 
@@ -171,6 +172,39 @@ def main():
                  "pool_ms": round(med(0), 4), "fwd_ms": round(med(1), 4), "bwd_ms": round(med(2), 4)}
         del ws_fg, ws_bg
 
+    # density sweep (outside the timed steps): mask + forward at 10 / 25 / 50 / 100 % of the blocks
+    # (fixed budget per row through the retention clamps), and the straight line through them
+    sweep = None
+    if not args.no_sweep:
+        pts = []
+        bufs_s = binding.alloc_index_lists(p)
+        for dd in (0.10, 0.25, 0.50, 1.00):
+            p_d = binding.Params(B=w.B, H=w.H, L=w.L, d=w.d, block=w.block, k_samples=w.k_samples,
+                                 tau=args.tau, r_min=dd, r_max=dd, n_prefix_dense=w.n_text)
+            s_ev = [[ev() for _ in range(3)] for _ in range(12)]   # 4 untimed repetitions first
+            for e3 in s_ev:
+                e3[0].record(stream)
+                binding.asa_build_mask(p_d, q, k, bufs_s["mask"], bufs_s["row_ptr"], bufs_s["col_idx"],
+                                       bufs_s["col_ptr"], bufs_s["row_idx"], None, ws_mask)
+                e3[1].record(stream)
+                binding.asa_attn_fwd(p_d, q, k, v, bufs_s["row_ptr"], bufs_s["col_idx"], o, lse, ws_fwd,
+                                     o_lo=None)
+                e3[2].record(stream)
+            torch.cuda.synchronize()
+            nnz_d = int(bufs_s["row_ptr"][:, -1].to(torch.int64).sum().item())
+            m_ms = float(np.median([e3[0].elapsed_time(e3[1]) for e3 in s_ev[4:]]))
+            f_ms = float(np.median([e3[1].elapsed_time(e3[2]) for e3 in s_ev[4:]]))
+            pts.append({"density": round(nnz_d / (p.B * p.H * p.Nb * p.Nb), 5), "mask_ms": round(m_ms, 4),
+                        "fwd_ms": round(f_ms, 4),
+                        "fwd_tflops": round(nnz_d * 4.0 * p.block * p.block * p.d / (f_ms * 1e-3) / 1e12, 1)})
+        xs = np.array([pt["density"] for pt in pts])
+        ys = np.array([pt["fwd_ms"] for pt in pts])
+        beta, alpha = np.polyfit(xs, ys, 1)
+        r2 = 1.0 - float(((ys - (alpha + beta * xs)) ** 2).sum() / ((ys - ys.mean()) ** 2).sum())
+        sweep = {"points": pts, "fit": "fwd_ms = alpha + beta * density", "alpha_ms": round(float(alpha), 4),
+                 "beta_ms": round(float(beta), 4), "r2": round(r2, 6)}
+        del bufs_s
+
     # Gilbert-curve rearrangement (done once per video, outside the timed steps): host time of the
     # order, the Q/K/V gather and the O scatter-back, and what it does to the density that the
     # threshold rule picks when the retention bounds are left open
@@ -267,6 +301,7 @@ def main():
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
         "asa_g": asa_g,
         "gilbert": gil,
+        "density_sweep": sweep,
         "roofline": {
             "kernel": (f"fwd_pp_kernel<{p.block},{p.d}>" if (p.block, p.d) == (128, 128)
                        else f"fwd_kernel<{p.block},{p.d}>"),
