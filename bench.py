@@ -172,6 +172,24 @@ def main():
                  "pool_ms": round(med(0), 4), "fwd_ms": round(med(1), 4), "bwd_ms": round(med(2), 4)}
         del ws_fg, ws_bg
 
+    # what the matrix cores and the memory system sustain on this device, measured in this run:
+    # a kernel of nothing but MFMAs (2 workgroups of 8 wavefronts per CU) and the plain copy that
+    # the V transposition of the forward call is (read once, written once)
+    measured = None
+    if not args.no_sweep:
+        sink = torch.empty(512 * 512, dtype=torch.float32, device="cuda")
+        m_ev = [(ev(), ev()) for _ in range(4)]
+        flop = 0.0
+        for a_ev, b_ev in m_ev:
+            binding.asa_set_kernel_timing(a_ev, b_ev)
+            flop = binding.asa_mfma_rate_probe(512, 4096, sink)
+        torch.cuda.synchronize()
+        mfma_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in m_ev[1:]]))
+        measured = {"mfma_only_tflops": round(flop / (mfma_ms * 1e-3) / 1e12, 1),
+                    "mfma_only_frac_of_published_peak": round(flop / (mfma_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                    "note": "independent 32x32x16 bf16 MFMAs only, 16 wavefronts per CU, %.2f ms" % mfma_ms}
+        del sink
+
     # density sweep (outside the timed steps): mask + forward at 10 / 25 / 50 / 100 % of the blocks
     # (fixed budget per row through the retention clamps), and the straight line through them
     sweep = None
@@ -302,6 +320,7 @@ def main():
         "asa_g": asa_g,
         "gilbert": gil,
         "density_sweep": sweep,
+        "measured_peaks": measured,
         "roofline": {
             "kernel": (f"fwd_pp_kernel<{p.block},{p.d}>" if (p.block, p.d) == (128, 128)
                        else f"fwd_kernel<{p.block},{p.d}>"),
@@ -311,6 +330,8 @@ def main():
             "unit": "TFLOP/s",
             "frac": round(float(kern_tflops / PEAK_BF16_TFLOPS), 4),
             "kernel_ms": round(float(kern_ms.mean()), 4),
+            "frac_of_measured_mfma_only_rate": (None if measured is None else
+                                                round(float(kern_tflops / measured["mfma_only_tflops"]), 4)),
             "flops_per_launch": fwd_flops,
             "traffic": (round(FWD_TRAFFIC_BYTES_WAN25) if (args.workload == "wan" and abs(dens - 0.25) < 1e-9
                                                            and args.seed == 42 and not args.no_bwd) else None),

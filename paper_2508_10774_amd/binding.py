@@ -41,7 +41,8 @@ EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_wo
            "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
            "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
            "asa_attn_bwd_g", "asa_mask_seeded_workspace_bytes", "asa_build_mask_seeded",
-           "asa_sample_offsets", "asa_gilbert_order", "asa_reorder_tokens"]
+           "asa_sample_offsets", "asa_gilbert_order", "asa_reorder_tokens",
+           "asa_mfma_rate_probe"]
 
 
 def load():
@@ -75,6 +76,8 @@ def load():
     L.asa_global_tokens.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp]
     L.asa_attn_fwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 11 + [ctypes.c_size_t, vp]
     L.asa_attn_bwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 17 + [ctypes.c_size_t, vp]
+    L.asa_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.asa_mfma_rate_probe.restype = ctypes.c_int
     L.asa_gilbert_order.argtypes = [ctypes.c_int32] * 4 + [vp, vp]
     L.asa_reorder_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
     for n in ("asa_gilbert_order", "asa_reorder_tokens", "asa_build_mask", "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd",
@@ -272,6 +275,14 @@ def asa_reorder_tokens(p: Params, src, dst, index, src_stride=None, dst_stride=N
     ds = (ctypes.c_int64 * 3)(*dst_stride) if dst_stride is not None else None
     _check(load().asa_reorder_tokens(ctypes.byref(p.c()), n, srcs, dsts, ss, ds, _ptr(index),
                                      _stream(stream)), "asa_reorder_tokens")
+
+
+def asa_mfma_rate_probe(workgroups: int, iters: int, sink, stream=None) -> float:
+    """Launch the MFMA-only calibration kernel; returns the FLOP of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(load().asa_mfma_rate_probe(workgroups, iters, _ptr(sink), ctypes.byref(flop), _stream(stream)),
+           "asa_mfma_rate_probe")
+    return flop.value
 
 
 def asa_set_kernel_timing(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):

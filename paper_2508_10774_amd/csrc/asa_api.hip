@@ -435,4 +435,12 @@ int asa_reorder_tokens(const asa_params *p, int32_t n_tensors, const void *const
                                reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
+int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, float *sink, double *flop,
+                        void *hip_stream) {
+  if (workgroups < 1 || workgroups > 65535 || iters < 1 || iters > (1 << 24) || !sink || !aligned4(sink))
+    return ASA_ERR_INVALID_ARG;
+  if (flop) *flop = (double)workgroups * 8.0 * 4.0 * (double)iters * (2.0 * 32 * 32 * 16);
+  return finish(launch_mfma_rate(workgroups, iters, sink, reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

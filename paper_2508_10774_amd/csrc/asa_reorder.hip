@@ -249,4 +249,40 @@ hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *s
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Calibration kernel for benchmarks: nothing but independent 32x32x16 bf16 MFMAs, 8 wavefronts
+// per CU on every CU, so that a report can put the rate the matrix cores sustain on this
+// device and at its clocks next to the published peak.  16 accumulators per wavefront are
+// four independent chains; results are stored so that nothing is optimised away.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, float *sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (bf16)(0.001f * (float)((threadIdx.x + i) & 7));
+    b[i] = (bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+  }
+  float r = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) r += acc[c][0] + acc[c][15];
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+// launches grid x 512 threads, each wavefront issuing 4 * iters MFMAs of 2 * 32 * 32 * 16 FLOP
+hipError_t launch_mfma_rate(int grid, int iters, float *sink, hipStream_t st) {
+  timing_begin(st);
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(512), 0, st, iters, sink);
+  timing_end(st);
+  return hipGetLastError();
+}
+
 }  // namespace asa
