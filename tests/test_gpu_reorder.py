@@ -121,3 +121,15 @@ def test_rearranged_tokens_through_mask_and_forward():
     util.assert_close_bf16(util.host_f32(o), want, "O in raster order")
     mask_raster, _ = oracle.build_mask(qf, kf, w.block, offs, 0.9)
     assert mask_g.mean() < mask_raster.mean()
+
+
+def test_mfma_rate_probe_runs_and_checks_its_arguments():
+    sink = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
+    flop = binding.asa_mfma_rate_probe(4, 8, sink)
+    torch.cuda.synchronize()
+    assert flop == 4 * 8 * 4 * 8 * 2 * 32 * 32 * 16
+    assert torch.isfinite(sink).all()
+    with pytest.raises(binding.AsaError):
+        binding.asa_mfma_rate_probe(0, 8, sink)
+    with pytest.raises(binding.AsaError):
+        binding.asa_mfma_rate_probe(4, 0, sink)
