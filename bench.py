@@ -185,10 +185,12 @@ def main():
             flop = binding.asa_mfma_rate_probe(512, 4096, sink)
         torch.cuda.synchronize()
         mfma_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in m_ev[1:]]))
+        sk = sink.view(512, 512)[:, :2].double().cpu().numpy()
         measured = {"mfma_only_tflops": round(flop / (mfma_ms * 1e-3) / 1e12, 1),
+                    "mfma_only_shader_clock_ghz": round(float(np.median(sk[:, 0] / sk[:, 1])) * 0.1, 3),
                     "mfma_only_frac_of_published_peak": round(flop / (mfma_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                     "note": "independent 32x32x16 bf16 MFMAs only, 16 wavefronts per CU, %.2f ms" % mfma_ms}
-        del sink
+        del sink, sk
 
     # density sweep (outside the timed steps): mask + forward at 10 / 25 / 50 / 100 % of the blocks
     # (fixed budget per row through the retention clamps), and the straight line through them

@@ -256,24 +256,37 @@ hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *s
 // four independent chains; results are stored so that nothing is optimised away.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, float *sink) {
-  bf16x8 a, b;
+  // four different operand pairs of pseudo-random bf16 values in [-1, 1): consecutive MFMAs see
+  // different data, as they do in a real kernel (identical operands switch far fewer gates and
+  // let the clock run higher than any real kernel's)
+  bf16x8 a[4], b[4];
+  uint32_t h = 0x9E3779B9u * (threadIdx.x + 1u) + 0x85EBCA6Bu * (blockIdx.x + 1u);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (bf16)(0.001f * (float)((threadIdx.x + i) & 7));
-    b[i] = (bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
-  }
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      h = h * 1664525u + 1013904223u;
+      a[c][i] = (bf16)((float)(int)(h >> 16 & 0xFFFF) * (1.0f / 32768.0f) - 1.0f);
+      h = h * 1664525u + 1013904223u;
+      b[c][i] = (bf16)((float)(int)(h >> 16 & 0xFFFF) * (1.0f / 32768.0f) - 1.0f);
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+  const long long t0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c], b[c], acc[c], 0, 0, 0);
   }
+  const long long t1 = clock64(), w1 = wall_clock64();
   float r = 0.f;
 #pragma unroll
   for (int c = 0; c < 4; ++c) r += acc[c][0] + acc[c][15];
+  // lane 0 of wavefront 0 reports shader-clock cycles and 100 MHz wall ticks of its loop instead
+  if (threadIdx.x == 0) r = (float)(t1 - t0);
+  if (threadIdx.x == 1) r = (float)(w1 - w0);
   sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
