@@ -123,6 +123,19 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
 
 // value of the other 32-lane half of the wavefront
 __device__ __forceinline__ float swap_halves(float x) { return __shfl_xor(x, 32, 64); }
+// max over the two 32-lane halves (lane i and lane i + 32), in every lane, by the register-file
+// lane swap of gfx950: v_permlane32_swap(a, b) exchanges the upper half of a with the lower half
+// of b; applied to two copies of x it leaves (x.lo, x.lo) and (x.hi, x.hi).  No trip through the
+// LDS crossbar, whose queue the matrix wavefronts keep full.
+__device__ __forceinline__ float max_of_halves(float x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t a = __builtin_bit_cast(uint32_t, x), b = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+#else
+  return x;
+#endif
+}
 #endif
 
 }  // namespace asa

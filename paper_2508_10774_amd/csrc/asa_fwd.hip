@@ -678,7 +678,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[mt][i]);
     request(kPortion);
-    mx = fmaxf(mx, swap_halves(mx)) * c + bias;
+    mx = max_of_halves(mx) * c + bias;
     if (__any(mx > m_run)) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = fast_exp2(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
