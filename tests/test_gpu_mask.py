@@ -45,6 +45,22 @@ def test_rule_kernel_is_bit_exact(Nb, tau, r_min, r_max):
     assert np.array_equal(got.cpu().numpy().reshape(-1, Nb), want)
 
 
+@pytest.mark.parametrize("Nb", [2, 63, 64, 65, 127, 128, 129, 255, 257, 511, 512, 513, 1023])
+def test_rule_kernel_at_the_edges_of_its_network_sizes(Nb):
+    """The sorting network is built for 128, 256, 512 or 1024 keys; rows just below, at and just
+    above those sizes (and rows shorter than a wavefront) against the oracle, bit for bit."""
+    H, block = 2, 64
+    p = binding.Params(B=1, H=H, L=Nb * block - 3, d=64, block=block, tau=0.8, r_min=0.05, r_max=0.9)
+    assert p.Nb == Nb
+    sc = _scores(H * Nb, Nb, seed=1000 + Nb) if Nb >= 16 else np.random.default_rng(Nb).random(
+        (H * Nb, Nb), dtype=np.float32)
+    want, _ = oracle.mask_rule(sc, 0.8, 0.05, 0.9)
+    got = torch.empty((H, Nb, Nb), dtype=torch.uint8, device="cuda")
+    binding.asa_mask_from_scores(p, torch.from_numpy(sc).cuda(), got)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().reshape(-1, Nb), want)
+
+
 def test_rule_kernel_forced_prefix():
     Nb, block = 20, 64
     p = binding.Params(B=1, H=2, L=Nb * block, d=64, block=block, tau=0.6, n_prefix_dense=130)
