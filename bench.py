@@ -133,6 +133,28 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3
 
+    # the same step captured into a HIP graph and replayed (the library allocates nothing and
+    # records no memset nodes): what is left of the step when the launches cost nothing
+    graph_ms = None
+    if not args.no_sweep:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        gr = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gr, stream=side):
+                step()      # (the binding launches on torch's current stream)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        t_g = time.perf_counter()
+        for _ in range(args.steps):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t_g) * 1e3 / args.steps
+        del gr
+
     # in-house dense baseline of the kernel-speedup ratio: the same forward call without index
     # lists (every key block), a few repetitions outside the timed steps
     dense_ms = None
@@ -292,6 +314,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(wall_ms / args.steps, 4),
+        "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
