@@ -32,7 +32,8 @@ def build(force: bool = False) -> str:
     """Compile asa_ref.c with gcc; returns the path of the shared library."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
-        cmd = ["gcc", "-std=c11", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared",
+        # (x86-64-v3, not native: the built library travels with the tree to other hosts)
+        cmd = ["gcc", "-std=c11", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared",
                "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
