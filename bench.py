@@ -176,6 +176,37 @@ def main():
         side_errors['dense_ref'] = repr(exc)
         torch.cuda.synchronize()
 
+    # the dense backward (no index lists) and the mask build with seeded per-block sampling, a few
+    # repetitions each
+    dense_bwd_ms = None
+    seeded_mask_ms = None
+    try:
+        if not args.no_dense_ref and not args.no_bwd:
+            d_ev = [(ev(), ev()) for _ in range(3)]
+            for a_ev, b_ev in d_ev:
+                a_ev.record(stream)
+                binding.asa_attn_bwd(p, q, k, v, o, g, lse, None, None, None, None, dq, dk, dv, ws_bwd,
+                                     o_lo=None)
+                b_ev.record(stream)
+            torch.cuda.synchronize()
+            dense_bwd_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[1:]]))
+        if not args.no_sweep:
+            ws_seed = binding.alloc_workspace(binding.asa_mask_seeded_workspace_bytes(p))
+            bufs_r = binding.alloc_index_lists(p)
+            d_ev = [(ev(), ev()) for _ in range(6)]
+            for a_ev, b_ev in d_ev:
+                a_ev.record(stream)
+                binding.asa_build_mask_seeded(p, args.seed, q, k, bufs_r["mask"], bufs_r["row_ptr"],
+                                              bufs_r["col_idx"], bufs_r["col_ptr"], bufs_r["row_idx"], None,
+                                              ws_seed)
+                b_ev.record(stream)
+            torch.cuda.synchronize()
+            seeded_mask_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[2:]]))
+            del ws_seed, bufs_r
+    except Exception as exc:   # noqa: BLE001
+        side_errors['dense_bwd_and_seeded_mask'] = repr(exc)
+        torch.cuda.synchronize()
+
     # ASA_G (global tokens, window n = block): pooling + forward + backward, outside the timed steps
     asa_g = None
     try:
@@ -365,6 +396,8 @@ def main():
         "dense_fwd_ms": None if dense_ms is None else round(dense_ms, 4),
         "dense_fwd_tflops": None if dense_ms is None else round(
             p.B * p.H * p.Nb * p.Nb * tile_flops / (dense_ms * 1e-3) / 1e12, 2),
+        "dense_bwd_ms": None if dense_bwd_ms is None else round(dense_bwd_ms, 4),
+        "seeded_sampling_mask_ms": None if seeded_mask_ms is None else round(seeded_mask_ms, 4),
         "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
         "asa_g": asa_g,
