@@ -53,6 +53,42 @@ def test_every_small_box_is_visited_once_and_in_unit_steps_where_parity_allows()
     assert n_clean > 300 and n_unclean > 100
 
 
+def _corner_walk_exists(a: int, b: int, c: int) -> bool:
+    """Exhaustive search: is there a walk in unit steps through every cell of the a x b x c box from
+    (0, 0, 0) to (a - 1, 0, 0)?"""
+    n = a * b * c
+    goal = (a - 1, 0, 0)
+    seen = {(0, 0, 0)}
+
+    def go(cell, left):
+        if left == 0:
+            return cell == goal
+        if cell == goal:
+            return False
+        x, y, z = cell
+        for nx, ny, nz in ((x + 1, y, z), (x - 1, y, z), (x, y + 1, z), (x, y - 1, z), (x, y, z + 1), (x, y, z - 1)):
+            if 0 <= nx < a and 0 <= ny < b and 0 <= nz < c and (nx, ny, nz) not in seen:
+                seen.add((nx, ny, nz))
+                if go((nx, ny, nz), left - 1):
+                    return True
+                seen.discard((nx, ny, nz))
+        return False
+
+    return go((0, 0, 0), n - 1)
+
+
+def test_the_parity_condition_is_exactly_when_a_corner_to_corner_walk_exists():
+    """Brute force on boxes of up to 24 cells: `clean` (the chess-board argument, a necessary
+    condition) is also sufficient there, so the curve's unit steps are all that could be had."""
+    n = 0
+    for a, b, c in itertools.product(range(1, 7), range(1, 5), range(1, 4)):
+        if a * b * c > 24:
+            continue
+        assert _corner_walk_exists(a, b, c) == gilbert.clean(a, b, c), (a, b, c)
+        n += 1
+    assert n > 40
+
+
 def _hilbert_d2xy(n: int, d: int):
     """Textbook conversion of a distance along the Hilbert curve of an n x n square (n = 2^k)
     to coordinates: per level take two bits, rotate/flip the quadrant, add the offset."""
