@@ -14,6 +14,8 @@
 //   dkv_kernel: queries on the M axis, keys on lanes: S = Q K^T, dP = dO V^T with K, V of the
 //               wave's 32 keys resident in registers; bf16(P) and bf16(dS) are the B operands of
 //               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T tiles from per-block transposed copies).
+#include <stdlib.h>
+
 #include "asa_common.hpp"
 #include "asa_tiles.hpp"
 
@@ -96,6 +98,7 @@ struct BwdCfg {
   static constexpr int kDqLds = (2 * kRowTile + kColTile) * 2;
   static constexpr int kDvLds = (kRowTile + kColTile) * 2 + 2 * kST * 4;
   static constexpr int kDkLds = (2 * kRowTile + kColTile) * 2 + 2 * kST * 4;
+  static constexpr int kDkvLds = (2 * kRowTile + 2 * kColTile) * 2 + 2 * kST * 4;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -262,15 +265,15 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
 // ---------------------------------------------------------------------------------------
 template <int BLK, int D, int WHAT>
 __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
-  constexpr bool DO_DV = WHAT == 0, DO_DK = WHAT == 1;
+  constexpr bool DO_DV = WHAT != 1, DO_DK = WHAT != 0, BOTH = WHAT == 2;
   using C = BwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
-  // dV uses {Q rows, dO^T slice}; dK uses {Q rows, dO rows, Q^T slice}
+  // dV uses {Q rows, dO^T slice}; dK uses {Q rows, dO rows, Q^T slice}; both: all four
   bf16 *Qs = reinterpret_cast<bf16 *>(smem);
-  bf16 *Gs = Qs + C::kRowTile;                       // dK only
-  bf16 *Qt = Gs + C::kRowTile;                       // dK only
-  bf16 *Gt = Qs + C::kRowTile;                       // dV only (same place as Gs)
-  float *sLse = reinterpret_cast<float *>(DO_DV ? Gt + C::kColTile : Qt + C::kColTile);
+  bf16 *Gs = Qs + C::kRowTile;                       // dK
+  bf16 *Qt = Gs + C::kRowTile;                       // dK
+  bf16 *Gt = BOTH ? Qt + C::kColTile : Qs + C::kRowTile;   // dV (alone: in the place of Gs)
+  float *sLse = reinterpret_cast<float *>((DO_DV ? Gt : Qt) + C::kColTile);
   float *sDelta = sLse + C::kST;
   __shared__ int rows[kMaxNb];
 
@@ -311,17 +314,24 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     if (DO_DK)
       vreg[s] = *reinterpret_cast<const bf16x8 *>(vs + (int64_t)krow_c * a.tv.sL + 16 * s + 8 * hl);
   }
-  f32x16 gacc[D / 32];   // dV^T (WHAT = 0) or dK^T (WHAT = 1) of my 32 keys
+  f32x16 gacc[D / 32];                 // dV^T (WHAT = 0) or dK^T (WHAT = 1, 2) of my 32 keys
+  f32x16 vacc[BOTH ? D / 32 : 1];      // dV^T when both are computed
 #pragma unroll
   for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
     for (int i = 0; i < 16; ++i) gacc[dm][i] = 0.f;
+#pragma unroll
+  for (int dm = 0; dm < (BOTH ? D / 32 : 1); ++dm)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vacc[dm][i] = 0.f;
 
   RowTileCopy<C::kST, D, C::kWaves> copy_q, copy_g;
   ColTileCopy<BLK, D, C::kWaves> copy_t;
-  copy_q.init(wave, lane, a.tq.sL);
-  copy_g.init(wave, lane, a.to.sL);
-  copy_t.init(wave, lane);
+  if (!BOTH) {
+    copy_q.init(wave, lane, a.tq.sL);
+    copy_g.init(wave, lane, a.to.sL);
+    copy_t.init(wave, lane);
+  }
 
   const int kr = kappa_b(n), cr = rho_b(n);
   const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
@@ -336,12 +346,25 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     const int i_blk = rows[step / C::kSub];
     const int sub = step % C::kSub;
     const int q0 = i_blk * BLK + sub * C::kST;
-    copy_q.issue(Qs, qs, q0, a.L);
-    if (DO_DK) {
-      copy_g.issue(Gs, gs, q0, a.L);
-      copy_t.issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST);
+    if constexpr (BOTH) {
+      // no offset tables here: with both accumulators and both operands resident, keeping them
+      // would spill, and a reload between two direct loads waits for the first to land
+      int lane_o = lane;
+      asm volatile("" : "+v"(lane_o));
+      using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
+      using ColCopy = LeanColTileCopy<BLK, D, C::kWaves>;
+      RowCopy::issue(Qs, qs, q0, a.L, a.tq.sL, wave, lane_o);
+      RowCopy::issue(Gs, gs, q0, a.L, a.to.sL, wave, lane_o);
+      ColCopy::issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST, wave, lane_o);
+      ColCopy::issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST, wave, lane_o);
     } else {
-      copy_t.issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST);
+      copy_q.issue(Qs, qs, q0, a.L);
+      if (DO_DK) {
+        copy_g.issue(Gs, gs, q0, a.L);
+        copy_t.issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST);
+      } else {
+        copy_t.issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST);
+      }
     }
     if (tid < C::kST) {
       const int r = q0 + tid;
@@ -351,6 +374,81 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
+    if constexpr (BOTH) {
+      // S -> P -> dV first, then dP -> dS -> dK, so that fewer registers are live at once
+#pragma unroll
+      for (int mt = 0; mt < C::kST / 32; ++mt) {
+        __builtin_amdgcn_s_setprio(0);
+        const bf16 *qrow = Qs + (mt * 32 + kr) * D;
+        const bf16 *grow = Gs + (mt * 32 + kr) * D;
+        f32x16 sacc = zero16;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+          bf16x8 qa = *reinterpret_cast<const bf16x8 *>(qrow + ((16 * s) ^ kx));
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
+        }
+        __builtin_amdgcn_s_setprio(3);
+        uint32_t pb[8];
+#pragma unroll
+        for (int t8 = 0; t8 < 2; ++t8) {
+          const int qq = mt * 32 + 16 * t8 + 8 * hl;
+          f32x4 l0 = *reinterpret_cast<const f32x4 *>(sLse + qq);
+          f32x4 l1 = *reinterpret_cast<const f32x4 *>(sLse + qq + 4);
+          float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const int i = 8 * t8 + e;
+            sacc[i] = kvalid ? fast_exp2(fmaf(sacc[i], c, -lv[e])) : 0.f;
+            sacc[i + 1] = kvalid ? fast_exp2(fmaf(sacc[i + 1], c, -lv[e + 1])) : 0.f;
+            pb[i >> 1] = pack_bf16x2(sacc[i], sacc[i + 1]);
+          }
+        }
+        __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          uint4 raw = make_uint4(pb[4 * tt], pb[4 * tt + 1], pb[4 * tt + 2], pb[4 * tt + 3]);
+          bf16x8 bp = *reinterpret_cast<bf16x8 *>(&raw);
+#pragma unroll
+          for (int dm = 0; dm < D / 32; ++dm) {
+            const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
+            bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Gt + off);
+            vacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bp, vacc[dm], 0, 0, 0);
+          }
+        }
+        f32x16 pacc = zero16;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+          bf16x8 ga = *reinterpret_cast<const bf16x8 *>(grow + ((16 * s) ^ kx));
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
+        }
+        __builtin_amdgcn_s_setprio(3);
+        uint32_t dsb[8];
+#pragma unroll
+        for (int t8 = 0; t8 < 2; ++t8) {
+          const int qq = mt * 32 + 16 * t8 + 8 * hl;
+          f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + qq);
+          f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + qq + 4);
+          float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const int i = 8 * t8 + e;
+            dsb[i >> 1] = pack_bf16x2(sacc[i] * (pacc[i] - dv[e]), sacc[i + 1] * (pacc[i + 1] - dv[e + 1]));
+          }
+        }
+        __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          uint4 raw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
+          bf16x8 bd = *reinterpret_cast<bf16x8 *>(&raw);
+#pragma unroll
+          for (int dm = 0; dm < D / 32; ++dm) {
+            const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
+            bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Qt + off);
+            gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bd, gacc[dm], 0, 0, 0);
+          }
+        }
+      }
+    } else {
 #pragma unroll
     for (int mt = 0; mt < C::kST / 32; ++mt) {
       __builtin_amdgcn_s_setprio(0);
@@ -395,10 +493,10 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
       __builtin_amdgcn_s_setprio(0);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        const uint32_t *w = DO_DV ? pb : dsb;
+        const uint32_t *w = DO_DK ? dsb : pb;
         uint4 raw = make_uint4(w[4 * tt], w[4 * tt + 1], w[4 * tt + 2], w[4 * tt + 3]);
         bf16x8 bf = *reinterpret_cast<bf16x8 *>(&raw);
-        const bf16 *tile = DO_DV ? Gt : Qt;   // dV^T += dO^T P,  dK^T += Q^T dS
+        const bf16 *tile = DO_DK ? Qt : Gt;   // dK^T += Q^T dS,  dV^T += dO^T P
 #pragma unroll
         for (int dm = 0; dm < D / 32; ++dm) {
           const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
@@ -407,33 +505,36 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
         }
       }
     }
+    }
   }
 
-  const float mul = DO_DV ? 1.f : a.scale;
-  float *out32 = DO_DV ? a.gv32 : a.gk32;
-  if (out32) {
-    // gradients of pooled tokens: kept in fp32 for the launch that spreads them over the windows
-    if (kvalid) {
-      float *row = out32 + (((int64_t)chunk * a.n_slabs + slab) * a.Nbk * BLK + krow) * D;
+  // epilogue of one gradient: acc holds its transpose for my 32 keys
+  auto emit = [&](f32x16 *acc, const bool is_dv) {
+    const float mul = is_dv ? 1.f : a.scale;
+    float *out32 = is_dv ? a.gv32 : a.gk32;
+    if (out32) {
+      // gradients of pooled tokens: kept in fp32 for the launch that spreads them over the windows
+      if (kvalid) {
+        float *row = out32 + (((int64_t)chunk * a.n_slabs + slab) * a.Nbk * BLK + krow) * D;
 #pragma unroll
-      for (int dm = 0; dm < D / 32; ++dm)
+        for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 v = {gacc[dm][4 * q4] * mul, gacc[dm][4 * q4 + 1] * mul, gacc[dm][4 * q4 + 2] * mul,
-                     gacc[dm][4 * q4 + 3] * mul};
-          *reinterpret_cast<f32x4 *>(row + dm * 32 + 16 * hl + 4 * q4) = v;
-        }
+          for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 v = {acc[dm][4 * q4] * mul, acc[dm][4 * q4 + 1] * mul, acc[dm][4 * q4 + 2] * mul,
+                       acc[dm][4 * q4 + 3] * mul};
+            *reinterpret_cast<f32x4 *>(row + dm * 32 + 16 * hl + 4 * q4) = v;
+          }
+      }
+      return;
     }
-    return;
-  }
-  if (kvalid) {
-    bf16 *out_row = DO_DV ? slab_ptr(a.dv, a.tv, slab, a.H) + (int64_t)krow * a.tv.sL
+    if (!kvalid) return;
+    bf16 *out_row = is_dv ? slab_ptr(a.dv, a.tv, slab, a.H) + (int64_t)krow * a.tv.sL
                           : slab_ptr(a.dk, a.tk, slab, a.H) + (int64_t)krow * a.tk.sL;
-    const float *pool = DO_DV ? a.pool_gv : a.pool_gk;
+    const float *pool = is_dv ? a.pool_gv : a.pool_gk;
 #pragma unroll
     for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) gacc[dm][i] *= mul;
+      for (int i = 0; i < 16; ++i) acc[dm][i] *= mul;
     if (pool) {
       // the mean over a window passes 1 / count of the pooled token's gradient to each token
       const int w = krow / a.pool_n;
@@ -446,7 +547,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
         for (int q4 = 0; q4 < 4; ++q4) {
           const f32x4 v = *reinterpret_cast<const f32x4 *>(prow + dm * 32 + 16 * hl + 4 * q4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) gacc[dm][4 * q4 + e] += v[e] * inv;
+          for (int e = 0; e < 4; ++e) acc[dm][4 * q4 + e] += v[e] * inv;
         }
     }
 #pragma unroll
@@ -454,12 +555,14 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
       uint32_t w[8];
 #pragma unroll
       for (int i = 0; i < 16; i += 2)
-        w[i >> 1] = pack_bf16x2(gacc[dm][i], gacc[dm][i + 1]);
+        w[i >> 1] = pack_bf16x2(acc[dm][i], acc[dm][i + 1]);
       uint4 *po = reinterpret_cast<uint4 *>(out_row + dm * 32 + 16 * hl);
       po[0] = make_uint4(w[0], w[1], w[2], w[3]);
       po[1] = make_uint4(w[4], w[5], w[6], w[7]);
     }
-  }
+  };
+  emit(gacc, WHAT == 0);
+  if (BOTH) emit(vacc, true);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -557,20 +660,31 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkLds);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkvLds);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
   hipError_t e = hipSuccess;
+  // dK and dV from one kernel (one S and P per tile for both); ASA_BWD_SPLIT_DKV selects the
+  // two single-gradient kernels instead (for A/B timing)
+  static const bool fused = getenv("ASA_BWD_SPLIT_DKV") == nullptr;
   timing_begin(st);
   if (pooled_launch) {
     // gradients of the pooled tokens first (fp32, every query block attends them) ...
     const BwdArgs &g = *pooled_launch;
     const int ggrid = xcd_grid(g.n_slabs * g.Nbk * g.q_chunks);
-    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, g);
-    e = hipGetLastError();
-    if (e == hipSuccess) {
-      hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, g);
+    if (fused) {
+      hipLaunchKernelGGL((dkv_kernel<BLK, D, 2>), dim3(ggrid), dim3(C::kThreads), C::kDkvLds, st, g);
       e = hipGetLastError();
+    } else {
+      hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, g);
+      e = hipGetLastError();
+      if (e == hipSuccess) {
+        hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, g);
+        e = hipGetLastError();
+      }
     }
     if (e == hipSuccess && g.q_chunks > 1) {
       const int64_t n4 = (int64_t)g.n_slabs * g.Nbk * BLK * D / 4;
@@ -581,11 +695,15 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
     }
   }
   // ... then the tokens' own gradients, which add their share of the pooled ones
-  if (e == hipSuccess) {
+  if (e == hipSuccess && fused) {
+    hipLaunchKernelGGL((dkv_kernel<BLK, D, 2>), dim3(grid), dim3(C::kThreads), C::kDkvLds, st, a);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess && !fused) {
     hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(grid), dim3(C::kThreads), C::kDvLds, st, a);
     e = hipGetLastError();
   }
-  if (e == hipSuccess) {
+  if (e == hipSuccess && !fused) {
     hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(grid), dim3(C::kThreads), C::kDkLds, st, a);
     e = hipGetLastError();
   }

@@ -193,6 +193,64 @@ struct ColTileCopy {
   }
 };
 
+// The same two copies for a kernel that cannot spare registers for the offset tables: nothing
+// is kept per lane, each offset is rebuilt from the lane number where it is used (a few integer
+// instructions per load).  The caller passes the lane number through an empty asm statement
+// inside its loop, so that the compiler does not hoist the offsets back into registers.
+template <int ROWS, int D, int WAVES>
+struct LeanRowTileCopy {
+  static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
+  static constexpr int kRowsPer = 64 / kChunks;               // rows per wave instruction
+  static constexpr int kInstr = ROWS * kChunks / 64 / WAVES;  // wave instructions per copy
+  static_assert((kInstr * kRowsPer) % 16 == 0, "a wave's first row must be a multiple of 16");
+
+  // copy rows [row0, row0 + ROWS) of `tensor` (slab base, row pitch sL elements) into `stage`;
+  // rows past L - 1 re-read row L - 1
+  static __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tensor, int row0, int L,
+                                               int64_t sL, int wave, int lane) {
+    const int64_t pitch = sL * 2;
+    const int lane_row = lane / kChunks, pos = lane % kChunks;
+    const char *base = reinterpret_cast<const char *>(tensor) + (int64_t)row0 * pitch;
+    const int lim = L - 1 - row0;   // last valid row of the tile
+    if (lim >= ROWS - 1) {
+      const uint32_t lane_row_off = (uint32_t)lane_row * (uint32_t)pitch;
+#pragma unroll
+      for (int i = 0; i < kInstr; ++i) {
+        const int r0 = (wave * kInstr + i) * kRowsPer;                    // wave-uniform
+        const int sw = k_swz<D>(((i * kRowsPer) & 15) + lane_row);        // = k_swz(r0 + lane_row)
+        const uint32_t lo = lane_row_off + (uint32_t)((pos ^ sw) * 16);
+        lds_dma16(base + (int64_t)r0 * pitch + lo, stage + (wave * kInstr + i) * 512);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < kInstr; ++i) {
+        const int row = (wave * kInstr + i) * kRowsPer + lane_row;
+        const int sw = k_swz<D>(row);
+        const int src_row = row > lim ? lim : row;                        // may be negative
+        lds_dma16(base + (int64_t)src_row * pitch + (pos ^ sw) * 16, stage + (wave * kInstr + i) * 512);
+      }
+    }
+  }
+};
+
+template <int BLK, int D, int WAVES>
+struct LeanColTileCopy {
+  static constexpr int kInstr = D * 8 / 64 / WAVES;
+  // columns [col0, col0 + 64) of the transposed tile `tile` ([D][BLK] bf16) into `stage`
+  static __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tile, int col0, int wave,
+                                               int lane) {
+    const char *base = reinterpret_cast<const char *>(tile + col0);
+    const int l8 = lane / 8, pos = lane % 8;
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int r0 = (wave * kInstr + i) * 8;                             // wave-uniform
+      const int sw = v_swz(r0 + l8);
+      const uint32_t lo = (uint32_t)((l8 * BLK + ((pos ^ sw) * 8)) * 2);
+      lds_dma16(base + (int64_t)r0 * BLK * 2 + lo, stage + (wave * kInstr + i) * 512);
+    }
+  }
+};
+
 // LDS address (elements) of the A fragment "row r, 16-byte chunk c" in the two images
 template <int D>
 __device__ __forceinline__ int row_tile_elem(int r, int c) { return r * D + ((c ^ k_swz<D>(r)) * 8); }
