@@ -98,7 +98,7 @@ struct BwdCfg {
   static constexpr int kDqLds = (2 * kRowTile + kColTile) * 2;
   static constexpr int kDvLds = (kRowTile + kColTile) * 2 + 2 * kST * 4;
   static constexpr int kDkLds = (2 * kRowTile + kColTile) * 2 + 2 * kST * 4;
-  static constexpr int kDkvLds = (2 * kRowTile + 2 * kColTile) * 2 + 2 * kST * 4;
+  static constexpr int kDkvLds = 2 * kRowTile * 2 + 2 * kST * 4;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -272,8 +272,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   bf16 *Qs = reinterpret_cast<bf16 *>(smem);
   bf16 *Gs = Qs + C::kRowTile;                       // dK
   bf16 *Qt = Gs + C::kRowTile;                       // dK
-  bf16 *Gt = BOTH ? Qt + C::kColTile : Qs + C::kRowTile;   // dV (alone: in the place of Gs)
-  float *sLse = reinterpret_cast<float *>((DO_DV ? Gt : Qt) + C::kColTile);
+  bf16 *Gt = Qs + C::kRowTile;                       // dV alone (in the place of Gs)
+  // both: Q rows and dO rows only; their transposes come from the transposing LDS read
+  float *sLse = reinterpret_cast<float *>(BOTH ? Qt : (DO_DV ? Gt : Qt) + C::kColTile);
   float *sDelta = sLse + C::kST;
   __shared__ int rows[kMaxNb];
 
@@ -334,7 +335,20 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   }
 
   const int kr = kappa_b(n), cr = rho_b(n);
-  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  const int kx = (hl ^ (BOTH ? t_swz<D>(kr) : k_swz<D>(kr))) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  // both: A operand "32 channels x 16 queries" of the products with P^T and dS^T, gathered from
+  // the row tiles.  Lane i of a 16-lane group addresses row (i / 4) of 4 consecutive queries and
+  // the 4 channels that the lanes 4 (i / 4) .. + 3 ... of the MFMA row order rho need
+  const lds_char *q_lds = (const lds_char *)Qs, *g_lds = (const lds_char *)Gs;
+  const int tr_i = lane & 15, tr_w = tr_i & 3, tr_j = tr_i >> 2, tr_b = (lane >> 4) & 1;
+  const uint32_t tr_lane = tr_piece<D>(8 * hl + tr_j, 16 * (tr_w & 1) + 8 * tr_b + 4 * (tr_w >> 1));
+  auto tr_operand = [&](const lds_char *tile, int mt, int tt, int dm) -> bf16x8 {
+    // queries 32 mt + 16 tt + 8 hl + (0..7) of channels 32 dm + rho(lane % 32)
+    const uint32_t x0 = (uint32_t)(((4 * dm) ^ t_swz<D>(0)) * 16), x1 = (uint32_t)(((4 * dm) ^ t_swz<D>(4)) * 16);
+    const bf16x4 lo = lds_read_tr16(tile + ((tr_lane ^ x0) + (uint32_t)((32 * mt + 16 * tt) * D * 2)));
+    const bf16x4 hi = lds_read_tr16(tile + ((tr_lane ^ x1) + (uint32_t)((32 * mt + 16 * tt + 4) * D * 2)));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
   const float c = a.scale_log2e;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -352,11 +366,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
       int lane_o = lane;
       asm volatile("" : "+v"(lane_o));
       using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
-      using ColCopy = LeanColTileCopy<BLK, D, C::kWaves>;
       RowCopy::issue(Qs, qs, q0, a.L, a.tq.sL, wave, lane_o);
       RowCopy::issue(Gs, gs, q0, a.L, a.to.sL, wave, lane_o);
-      ColCopy::issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST, wave, lane_o);
-      ColCopy::issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST, wave, lane_o);
     } else {
       copy_q.issue(Qs, qs, q0, a.L);
       if (DO_DK) {
@@ -410,9 +421,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
           bf16x8 bp = *reinterpret_cast<bf16x8 *>(&raw);
 #pragma unroll
           for (int dm = 0; dm < D / 32; ++dm) {
-            const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
-            bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Gt + off);
-            vacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bp, vacc[dm], 0, 0, 0);
+            vacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(g_lds, mt, tt, dm), bp, vacc[dm], 0, 0, 0);
           }
         }
         f32x16 pacc = zero16;
@@ -442,9 +451,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
           bf16x8 bd = *reinterpret_cast<bf16x8 *>(&raw);
 #pragma unroll
           for (int dm = 0; dm < D / 32; ++dm) {
-            const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
-            bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Qt + off);
-            gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bd, gacc[dm], 0, 0, 0);
+            gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(q_lds, mt, tt, dm), bd, gacc[dm], 0, 0, 0);
           }
         }
       }

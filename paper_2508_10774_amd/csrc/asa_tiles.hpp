@@ -38,6 +38,32 @@ __device__ __forceinline__ int k_swz(int row) {
 __device__ __forceinline__ int v_swz(int row) { return ((row >> 1) & 3) | (((row >> 4) & 1) << 2); }
 
 typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+// Swizzle of a row tile that is read both row-wise (16 lanes, 16 rows, one 16-byte chunk) and
+// through the transposing LDS read (16 lanes: 4 consecutive rows x four 8-byte pieces).  With
+// D = 128 the row's low two bits go to the chunk's high two bits, so that the 4 consecutive rows
+// of a transposing read fall into 4 different quarters of the banks; any bijection of row mod 16
+// serves the row-wise reads.  With D = 64 the k_swz pattern already serves both.
+template <int D>
+__device__ __forceinline__ int t_swz(int row) {
+  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((row >> 1) & 7);
+}
+// byte offset, in a t_swz row tile, of the 8-byte piece "row r, columns d4 .. d4 + 3" (d4 % 4 == 0)
+template <int D>
+__device__ __forceinline__ uint32_t tr_piece(int r, int d4) {
+  return (uint32_t)((r * D + (((d4 >> 3) ^ t_swz<D>(r)) << 3) + (d4 & 4)) * 2);
+}
+// ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives as element j (j = 0..3) the
+// 16-bit element i % 4 of the 8 bytes that lane 4 j + i / 4 of the group addressed.
+__device__ __forceinline__ bf16x4 lds_read_tr16(const lds_char *p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)p);
+#else
+  return bf16x4{};
+#endif
+}
 
 // One direct global->LDS load: every lane fetches 16 bytes from its own global address and the
 // wavefront's 64 x 16 B land contiguously at the (wave-uniform) LDS address.  Counted by vmcnt.
@@ -193,7 +219,7 @@ struct ColTileCopy {
   }
 };
 
-// The same two copies for a kernel that cannot spare registers for the offset tables: nothing
+// The same two copies (the row tile with the t_swz swizzle) for a kernel that cannot spare registers for the offset tables: nothing
 // is kept per lane, each offset is rebuilt from the lane number where it is used (a few integer
 // instructions per load).  The caller passes the lane number through an empty asm statement
 // inside its loop, so that the compiler does not hoist the offsets back into registers.
@@ -217,7 +243,7 @@ struct LeanRowTileCopy {
 #pragma unroll
       for (int i = 0; i < kInstr; ++i) {
         const int r0 = (wave * kInstr + i) * kRowsPer;                    // wave-uniform
-        const int sw = k_swz<D>(((i * kRowsPer) & 15) + lane_row);        // = k_swz(r0 + lane_row)
+        const int sw = t_swz<D>(((i * kRowsPer) & 15) + lane_row);        // = t_swz(r0 + lane_row)
         const uint32_t lo = lane_row_off + (uint32_t)((pos ^ sw) * 16);
         lds_dma16(base + (int64_t)r0 * pitch + lo, stage + (wave * kInstr + i) * 512);
       }
@@ -225,7 +251,7 @@ struct LeanRowTileCopy {
 #pragma unroll
       for (int i = 0; i < kInstr; ++i) {
         const int row = (wave * kInstr + i) * kRowsPer + lane_row;
-        const int sw = k_swz<D>(row);
+        const int sw = t_swz<D>(row);
         const int src_row = row > lim ? lim : row;                        // may be negative
         lds_dma16(base + (int64_t)src_row * pitch + (pos ^ sw) * 16, stage + (wave * kInstr + i) * 512);
       }
