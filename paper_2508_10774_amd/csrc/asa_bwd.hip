@@ -1,7 +1,7 @@
 // Block-sparse attention backward for gfx950, mask held constant (the paper restricts attention
 // with the block mask "during both training and inference", Sec. 3.3 Step 2.1).
 //
-//   Delta = rowsum(dO * O)                        delta_kernel
+//   Delta = rowsum(dO * O), LSE in log2 units     delta_kernel (both padded to whole blocks)
 //   dQ    = scale * dS K     per query block      dq_kernel   (walks the row list, CSR)
 //   dK    = scale * dS^T Q,  dV = P^T dO  per key block   dkv_kernel  (walks the column list, CSC)
 // with P = exp(scale*S - LSE), dS = P * (dO V^T - Delta) recomputed per tile in both kernels,
@@ -13,8 +13,11 @@
 //               the B operand of dQ^T = K^T dS^T (K^T tiles come from a per-block transposed copy of K).
 //   dkv_kernel: queries on the M axis, keys on lanes: S = Q K^T, dP = dO V^T with K, V of the
 //               wave's 32 keys resident in registers; bf16(P) and bf16(dS) are the B operands of
-//               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T tiles from per-block transposed copies).
+//               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T operands by transposing LDS reads of
+//               the row tiles).
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "asa_common.hpp"
 #include "asa_tiles.hpp"
@@ -27,12 +30,18 @@ __device__ __forceinline__ int rho_b(int r) { return rho(r); }
 constexpr float kLog2e = 1.44269504088896340736f;
 
 // ---------------------------------------------------------------------------------------
-// Delta[slab][row] = sum_x dO[row][x] * (O[row][x] + O_lo[row][x])   (fp32).  16 lanes per row.
+// Row statistics of the backward, padded to whole blocks (pitch Lpad) so that the kernels can
+// fetch 64 of them without a bounds test:
+//   delta[slab][row] = sum_x dO[row][x] * (O[row][x] + O_lo[row][x])  (fp32), 0 past L
+//   lse2[slab][row]  = LSE[row] * log2(e), +inf past L (every probability of such a row is 0)
+//   lse2g            = lse2 - bias (for keys whose scores carry an additive bias), if asked for
+// 16 lanes per row.
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const void *o, const void *o_lo,
                                                     const void *d_o, TensorView to, int H, int L,
-                                                    float *delta) {
+                                                    int Lpad, const float *lse, float bias_log2,
+                                                    float *delta, float *lse2, float *lse2g) {
   const int slab = blockIdx.y;
   const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int sub = threadIdx.x & 15;
@@ -59,13 +68,19 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *o, const void *o
   acc += __shfl_xor(acc, 4, 64);
   acc += __shfl_xor(acc, 2, 64);
   acc += __shfl_xor(acc, 1, 64);
-  if (row < L && sub == 0) delta[(int64_t)slab * L + row] = acc;
+  if (row < Lpad && sub == 0) {
+    const int64_t at = (int64_t)slab * Lpad + row;
+    const float l2 = row < L ? lse[(int64_t)slab * L + row] * kLog2e : INFINITY;
+    delta[at] = acc;
+    lse2[at] = l2;
+    if (lse2g) lse2g[at] = l2 - bias_log2;
+  }
 }
 
 struct BwdArgs {
   const void *q, *k, *v, *d_o;
-  const bf16 *qt, *kt, *dot;  // [slab][Nb][d][block] transposed-tile copies of Q, K, dO
-  const float *lse, *delta;
+  const bf16 *kt;             // [slab][Nb][d][block] transposed-tile copy of K (dQ kernel)
+  const float *lse2, *delta;  // [slab][Lpad]: LSE * log2(e) (minus this launch's key bias), Delta; padded with +inf, 0
   const int32_t *row_ptr, *col_idx, *col_ptr, *row_idx;
   void *dq, *dk, *dv;
   TensorView tq, tk, tv, to;
@@ -75,7 +90,6 @@ struct BwdArgs {
   // ---- global tokens of ASA_G (all zero / null when they are not used)
   // dK/dV kernels: the key side of a launch may be the pooled tokens instead of K, V
   int Lk, Nbk;            // valid key rows and key blocks of this launch (= L, Nb normally)
-  float key_bias_log2;    // added to the scaled scores of this launch's keys (log2 domain)
   float *gk32, *gv32;     // non-null: write fp32 gradients [chunk][slab][Nbk * block][d] here instead of dk / dv
   int q_chunks;           // with gk32 / gv32: the query blocks are split into this many ranges, one workgroup each
   const float *pool_gk, *pool_gv;   // non-null: add pool_g*[slab][row / pool_n] / count(window) to row's gradient
@@ -96,9 +110,8 @@ struct BwdCfg {
   static constexpr int kRowTile = kST * D;       // [64][D]  elements, swizzled, unpadded
   static constexpr int kColTile = D * kST;       // [D][64]
   static constexpr int kDqLds = (2 * kRowTile + kColTile) * 2;
-  static constexpr int kDvLds = (kRowTile + kColTile) * 2 + 2 * kST * 4;
-  static constexpr int kDkLds = (2 * kRowTile + kColTile) * 2 + 2 * kST * 4;
-  static constexpr int kDkvLds = 2 * kRowTile * 2 + 2 * kST * 4;
+  static constexpr int kDkvStage = 2 * kRowTile * 2 + 2 * kST * 4;   // Q rows, dO rows, LSE, Delta
+  static constexpr int kDkvLds = 2 * kDkvStage;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -152,9 +165,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     qreg[s] = *reinterpret_cast<const bf16x8 *>(qs + (int64_t)qrow_c * a.tq.sL + 16 * s + 8 * hl);
     greg[s] = *reinterpret_cast<const bf16x8 *>(gs + (int64_t)qrow_c * a.to.sL + 16 * s + 8 * hl);
   }
-  // rows past L get LSE = +inf, so that every probability is exactly zero
-  const float lse2 = qvalid ? a.lse[(int64_t)slab * a.L + qrow] * kLog2e : INFINITY;
-  const float delta = qvalid ? a.delta[(int64_t)slab * a.L + qrow] : 0.f;
+  // rows past L have LSE = +inf there, so that every probability is exactly zero
+  const float lse2 = a.lse2[(int64_t)slab * a.Lpad + qrow];
+  const float delta = a.delta[(int64_t)slab * a.Lpad + qrow];
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -256,27 +269,23 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// dK, dV: one workgroup per key block, one wavefront per 32 keys (its K and V rows stay in
-// registers as B operands).  Per step of 64 queries: Q rows, dO rows, Q^T and dO^T slices,
-// LSE and Delta go to LDS.  The kernel is instantiated twice, WHAT = 0 for dV (needs S and P
-// only) and WHAT = 1 for dK (needs S, dP and dS): holding both 32 x d fp32 accumulators plus
-// the K and V operands in one wavefront exceeds the register budget of two wavefronts per
-// SIMD, and recomputing S (one extra tile product) is cheaper than running at half occupancy.
+// dK, dV: one workgroup per key block, one wavefront per 32 keys; its K and V rows stay in
+// registers as B operands and both 32 x d fp32 accumulators live in registers, so S and P are
+// computed once per tile for both gradients.  Per step of 64 queries the workgroup copies Q rows
+// and dO rows (and the 64 LSE and Delta values) into one of two LDS stages while it works on
+// the other.  The products with P^T and dS^T need "channels x queries" operands: they are
+// gathered from the same row tiles by the transposing LDS read, so no transposed copy of Q or
+// dO exists, in LDS or in memory.  The register file is full (2 wavefronts per SIMD at 256
+// registers): per-lane copy offsets are rebuilt at each use instead of kept.
 // ---------------------------------------------------------------------------------------
-template <int BLK, int D, int WHAT>
+template <int BLK, int D>
 __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
-  constexpr bool DO_DV = WHAT != 1, DO_DK = WHAT != 0, BOTH = WHAT == 2;
   using C = BwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
-  // dV uses {Q rows, dO^T slice}; dK uses {Q rows, dO rows, Q^T slice}; both: all four
-  bf16 *Qs = reinterpret_cast<bf16 *>(smem);
-  bf16 *Gs = Qs + C::kRowTile;                       // dK
-  bf16 *Qt = Gs + C::kRowTile;                       // dK
-  bf16 *Gt = Qs + C::kRowTile;                       // dV alone (in the place of Gs)
-  // both: Q rows and dO rows only; their transposes come from the transposing LDS read
-  float *sLse = reinterpret_cast<float *>(BOTH ? Qt : (DO_DV ? Gt : Qt) + C::kColTile);
-  float *sDelta = sLse + C::kST;
   __shared__ int rows[kMaxNb];
+  // a stage: Q rows [64][D], dO rows [64][D] (t_swz images), LSE [64], Delta [64]
+  constexpr int kStage = C::kDkvStage;
+  constexpr int kGOff = C::kRowTile * 2, kLseOff = 2 * C::kRowTile * 2, kDeltaOff = kLseOff + C::kST * 4;
 
   const int work_c = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nbk * a.q_chunks);
   if (work_c < 0) return;
@@ -292,8 +301,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vs = slab_ptr(a.v, a.tv, slab, a.H);
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
-  const bf16 *qts = a.qt + (int64_t)slab * D * a.Lpad;
-  const bf16 *gts = a.dot + (int64_t)slab * D * a.Lpad;
+  const float *lse_s = a.lse2 + (int64_t)slab * a.Lpad;      // padded: every copy is 64 whole values
+  const float *delta_s = a.delta + (int64_t)slab * a.Lpad;
   const bool dense = a.col_ptr == nullptr;   // no index lists: every query block
   const int t_begin = dense ? 0 : a.col_ptr[slab * (a.Nb + 1) + kb];
   const int per_chunk = (a.Nb + a.q_chunks - 1) / a.q_chunks;
@@ -312,206 +321,126 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     kreg[s] = *reinterpret_cast<const bf16x8 *>(ks + (int64_t)krow_c * a.tk.sL + 16 * s + 8 * hl);
-    if (DO_DK)
-      vreg[s] = *reinterpret_cast<const bf16x8 *>(vs + (int64_t)krow_c * a.tv.sL + 16 * s + 8 * hl);
+    vreg[s] = *reinterpret_cast<const bf16x8 *>(vs + (int64_t)krow_c * a.tv.sL + 16 * s + 8 * hl);
   }
-  f32x16 gacc[D / 32];                 // dV^T (WHAT = 0) or dK^T (WHAT = 1, 2) of my 32 keys
-  f32x16 vacc[BOTH ? D / 32 : 1];      // dV^T when both are computed
+  f32x16 kacc[D / 32], vacc[D / 32];   // dK^T and dV^T of my 32 keys
 #pragma unroll
   for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) gacc[dm][i] = 0.f;
-#pragma unroll
-  for (int dm = 0; dm < (BOTH ? D / 32 : 1); ++dm)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) vacc[dm][i] = 0.f;
+    for (int i = 0; i < 16; ++i) kacc[dm][i] = vacc[dm][i] = 0.f;
 
-  RowTileCopy<C::kST, D, C::kWaves> copy_q, copy_g;
-  ColTileCopy<BLK, D, C::kWaves> copy_t;
-  if (!BOTH) {
-    copy_q.init(wave, lane, a.tq.sL);
-    copy_g.init(wave, lane, a.to.sL);
-    copy_t.init(wave, lane);
-  }
-
-  const int kr = kappa_b(n), cr = rho_b(n);
-  const int kx = (hl ^ (BOTH ? t_swz<D>(kr) : k_swz<D>(kr))) * 8, cx = (hl ^ v_swz(cr)) * 8;
-  // both: A operand "32 channels x 16 queries" of the products with P^T and dS^T, gathered from
-  // the row tiles.  Lane i of a 16-lane group addresses row (i / 4) of 4 consecutive queries and
-  // the 4 channels that the lanes 4 (i / 4) .. + 3 ... of the MFMA row order rho need
-  const lds_char *q_lds = (const lds_char *)Qs, *g_lds = (const lds_char *)Gs;
+  // row-wise A fragments (S = Q K^T, dP = dO V^T): row kappa(n) of a 32-query group
+  const int kr = kappa_b(n);
+  const int kx = (hl ^ t_swz<D>(kr)) * 8;
+  // transposed A fragments "32 channels x 16 queries" (dV^T += dO^T P, dK^T += Q^T dS): lane i of
+  // a 16-lane group addresses query i / 4 of 4 consecutive ones and 4 of the channels that
+  // the MFMA rows of its group stand for (row order rho); two reads make the 8 queries of a lane
+  const lds_char *smem_lds = (const lds_char *)smem;
   const int tr_i = lane & 15, tr_w = tr_i & 3, tr_j = tr_i >> 2, tr_b = (lane >> 4) & 1;
   const uint32_t tr_lane = tr_piece<D>(8 * hl + tr_j, 16 * (tr_w & 1) + 8 * tr_b + 4 * (tr_w >> 1));
-  auto tr_operand = [&](const lds_char *tile, int mt, int tt, int dm) -> bf16x8 {
-    // queries 32 mt + 16 tt + 8 hl + (0..7) of channels 32 dm + rho(lane % 32)
-    const uint32_t x0 = (uint32_t)(((4 * dm) ^ t_swz<D>(0)) * 16), x1 = (uint32_t)(((4 * dm) ^ t_swz<D>(4)) * 16);
-    const bf16x4 lo = lds_read_tr16(tile + ((tr_lane ^ x0) + (uint32_t)((32 * mt + 16 * tt) * D * 2)));
-    const bf16x4 hi = lds_read_tr16(tile + ((tr_lane ^ x1) + (uint32_t)((32 * mt + 16 * tt + 4) * D * 2)));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  };
   const float c = a.scale_log2e;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_steps = n_tiles * C::kSub;
+  auto issue = [&](int step, int stage) {
+    const int q0 = rows[step / C::kSub] * BLK + (step % C::kSub) * C::kST;
+    int lane_o = lane;
+    asm volatile("" : "+v"(lane_o));   // offsets are rebuilt here, not hoisted into registers
+    using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
+    unsigned char *st = smem + stage * kStage;
+    RowCopy::issue(reinterpret_cast<bf16 *>(st), qs, q0, a.L, a.tq.sL, wave, lane_o);
+    RowCopy::issue(reinterpret_cast<bf16 *>(st + kGOff), gs, q0, a.L, a.to.sL, wave, lane_o);
+    if (wave == 0) lds_dma4(lse_s + q0 + lane_o, st + kLseOff);
+    if (wave == 1) lds_dma4(delta_s + q0 + lane_o, st + kDeltaOff);
+  };
+  __syncthreads();   // rows[] is written
+  if (n_steps > 0) issue(0, 0);
   for (int step = 0; step < n_steps; ++step) {
     __builtin_amdgcn_s_setprio(3);
-    __syncthreads();
-    const int i_blk = rows[step / C::kSub];
-    const int sub = step % C::kSub;
-    const int q0 = i_blk * BLK + sub * C::kST;
-    if constexpr (BOTH) {
-      // no offset tables here: with both accumulators and both operands resident, keeping them
-      // would spill, and a reload between two direct loads waits for the first to land
-      int lane_o = lane;
-      asm volatile("" : "+v"(lane_o));
-      using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
-      RowCopy::issue(Qs, qs, q0, a.L, a.tq.sL, wave, lane_o);
-      RowCopy::issue(Gs, gs, q0, a.L, a.to.sL, wave, lane_o);
-    } else {
-      copy_q.issue(Qs, qs, q0, a.L);
-      if (DO_DK) {
-        copy_g.issue(Gs, gs, q0, a.L);
-        copy_t.issue(Qt, qts + (int64_t)i_blk * D * BLK, sub * C::kST);
-      } else {
-        copy_t.issue(Gt, gts + (int64_t)i_blk * D * BLK, sub * C::kST);
-      }
-    }
-    if (tid < C::kST) {
-      const int r = q0 + tid;
-      const bool ok = r < a.L;
-      sLse[tid] = ok ? a.lse[(int64_t)slab * a.L + r] * kLog2e - a.key_bias_log2 : INFINITY;
-      if (DO_DK) sDelta[tid] = ok ? a.delta[(int64_t)slab * a.L + r] : 0.f;
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    if constexpr (BOTH) {
-      // S -> P -> dV first, then dP -> dS -> dK, so that fewer registers are live at once
-#pragma unroll
-      for (int mt = 0; mt < C::kST / 32; ++mt) {
-        __builtin_amdgcn_s_setprio(0);
-        const bf16 *qrow = Qs + (mt * 32 + kr) * D;
-        const bf16 *grow = Gs + (mt * 32 + kr) * D;
-        f32x16 sacc = zero16;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-          bf16x8 qa = *reinterpret_cast<const bf16x8 *>(qrow + ((16 * s) ^ kx));
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
-        }
-        __builtin_amdgcn_s_setprio(3);
-        uint32_t pb[8];
-#pragma unroll
-        for (int t8 = 0; t8 < 2; ++t8) {
-          const int qq = mt * 32 + 16 * t8 + 8 * hl;
-          f32x4 l0 = *reinterpret_cast<const f32x4 *>(sLse + qq);
-          f32x4 l1 = *reinterpret_cast<const f32x4 *>(sLse + qq + 4);
-          float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const int i = 8 * t8 + e;
-            sacc[i] = kvalid ? fast_exp2(fmaf(sacc[i], c, -lv[e])) : 0.f;
-            sacc[i + 1] = kvalid ? fast_exp2(fmaf(sacc[i + 1], c, -lv[e + 1])) : 0.f;
-            pb[i >> 1] = pack_bf16x2(sacc[i], sacc[i + 1]);
-          }
-        }
-        __builtin_amdgcn_s_setprio(0);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          uint4 raw = make_uint4(pb[4 * tt], pb[4 * tt + 1], pb[4 * tt + 2], pb[4 * tt + 3]);
-          bf16x8 bp = *reinterpret_cast<bf16x8 *>(&raw);
-#pragma unroll
-          for (int dm = 0; dm < D / 32; ++dm) {
-            vacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(g_lds, mt, tt, dm), bp, vacc[dm], 0, 0, 0);
-          }
-        }
-        f32x16 pacc = zero16;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-          bf16x8 ga = *reinterpret_cast<const bf16x8 *>(grow + ((16 * s) ^ kx));
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
-        }
-        __builtin_amdgcn_s_setprio(3);
-        uint32_t dsb[8];
-#pragma unroll
-        for (int t8 = 0; t8 < 2; ++t8) {
-          const int qq = mt * 32 + 16 * t8 + 8 * hl;
-          f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + qq);
-          f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + qq + 4);
-          float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const int i = 8 * t8 + e;
-            dsb[i >> 1] = pack_bf16x2(sacc[i] * (pacc[i] - dv[e]), sacc[i + 1] * (pacc[i + 1] - dv[e + 1]));
-          }
-        }
-        __builtin_amdgcn_s_setprio(0);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          uint4 raw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
-          bf16x8 bd = *reinterpret_cast<bf16x8 *>(&raw);
-#pragma unroll
-          for (int dm = 0; dm < D / 32; ++dm) {
-            gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(q_lds, mt, tt, dm), bd, gacc[dm], 0, 0, 0);
-          }
-        }
-      }
-    } else {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): my copies of this step have landed
+    __syncthreads();                      // everyone's have; everyone is done with the other stage
+    const int stage = step & 1;
+    if (step + 1 < n_steps) issue(step + 1, stage ^ 1);
+    const bf16 *Qs = reinterpret_cast<const bf16 *>(smem + stage * kStage);
+    const bf16 *Gs = Qs + C::kRowTile;
+    const float *sLse = reinterpret_cast<const float *>(smem + stage * kStage + kLseOff);
+    const float *sDelta = sLse + C::kST;
+    const uint32_t tr_base = tr_lane + (uint32_t)(stage * kStage);   // kStage % 512 == 0
+    auto tr_operand = [&](int tile_bytes, int mt, int tt, int dm) -> bf16x8 {
+      // queries 32 mt + 16 tt + 8 hl + (0..7) of channels 32 dm + rho(lane % 32)
+      const uint32_t x0 = (uint32_t)(((4 * dm) ^ t_swz<D>(0)) * 16), x1 = (uint32_t)(((4 * dm) ^ t_swz<D>(4)) * 16);
+      const bf16x4 lo = lds_read_tr16(smem_lds + ((tr_base ^ x0) + (uint32_t)(tile_bytes + (32 * mt + 16 * tt) * D * 2)));
+      const bf16x4 hi = lds_read_tr16(smem_lds + ((tr_base ^ x1) + (uint32_t)(tile_bytes + (32 * mt + 16 * tt + 4) * D * 2)));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    // S -> P -> dV first, then dP -> dS -> dK, so that fewer registers are live at once
 #pragma unroll
     for (int mt = 0; mt < C::kST / 32; ++mt) {
       __builtin_amdgcn_s_setprio(0);
       const bf16 *qrow = Qs + (mt * 32 + kr) * D;
       const bf16 *grow = Gs + (mt * 32 + kr) * D;
-      f32x16 sacc = zero16, pacc = zero16;
+      f32x16 sacc = zero16;
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
         bf16x8 qa = *reinterpret_cast<const bf16x8 *>(qrow + ((16 * s) ^ kx));
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
-        if (DO_DK) {
-          bf16x8 ga = *reinterpret_cast<const bf16x8 *>(grow + ((16 * s) ^ kx));
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
-        }
       }
       // accumulator register i of lane half hl is query 32mt + 16(i/8) + 8hl + (i%8)
-      uint32_t pb[8], dsb[8];
       __builtin_amdgcn_s_setprio(3);   // vector work goes ahead of the other workgroup's MFMA stream
+      uint32_t pb[8];
 #pragma unroll
       for (int t8 = 0; t8 < 2; ++t8) {
         const int qq = mt * 32 + 16 * t8 + 8 * hl;
         f32x4 l0 = *reinterpret_cast<const f32x4 *>(sLse + qq);
         f32x4 l1 = *reinterpret_cast<const f32x4 *>(sLse + qq + 4);
         float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
-        float dv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (DO_DK) {
-          f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + qq);
-          f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + qq + 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { dv[e] = d0[e]; dv[4 + e] = d1[e]; }
-        }
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
           const int i = 8 * t8 + e;
-          float p0 = kvalid ? fast_exp2(fmaf(sacc[i], c, -lv[e])) : 0.f;
-          float p1 = kvalid ? fast_exp2(fmaf(sacc[i + 1], c, -lv[e + 1])) : 0.f;
-          if (DO_DV) pb[i >> 1] = pack_bf16x2(p0, p1);
-          if (DO_DK)
-            dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - dv[e]), p1 * (pacc[i + 1] - dv[e + 1]));
+          sacc[i] = kvalid ? fast_exp2(fmaf(sacc[i], c, -lv[e])) : 0.f;
+          sacc[i + 1] = kvalid ? fast_exp2(fmaf(sacc[i + 1], c, -lv[e + 1])) : 0.f;
+          pb[i >> 1] = pack_bf16x2(sacc[i], sacc[i + 1]);
         }
       }
       __builtin_amdgcn_s_setprio(0);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        const uint32_t *w = DO_DK ? dsb : pb;
-        uint4 raw = make_uint4(w[4 * tt], w[4 * tt + 1], w[4 * tt + 2], w[4 * tt + 3]);
-        bf16x8 bf = *reinterpret_cast<bf16x8 *>(&raw);
-        const bf16 *tile = DO_DK ? Qt : Gt;   // dK^T += Q^T dS,  dV^T += dO^T P
+        uint4 raw = make_uint4(pb[4 * tt], pb[4 * tt + 1], pb[4 * tt + 2], pb[4 * tt + 3]);
+        bf16x8 bp = *reinterpret_cast<bf16x8 *>(&raw);
 #pragma unroll
-        for (int dm = 0; dm < D / 32; ++dm) {
-          const int off = (dm * 32 + cr) * C::kST + ((16 * (2 * mt + tt)) ^ cx);
-          bf16x8 ta = *reinterpret_cast<const bf16x8 *>(tile + off);
-          gacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, bf, gacc[dm], 0, 0, 0);
+        for (int dm = 0; dm < D / 32; ++dm)
+          vacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(kGOff, mt, tt, dm), bp, vacc[dm], 0, 0, 0);
+      }
+      f32x16 pacc = zero16;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) {
+        bf16x8 ga = *reinterpret_cast<const bf16x8 *>(grow + ((16 * s) ^ kx));
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], pacc, 0, 0, 0);
+      }
+      __builtin_amdgcn_s_setprio(3);
+      uint32_t dsb[8];
+#pragma unroll
+      for (int t8 = 0; t8 < 2; ++t8) {
+        const int qq = mt * 32 + 16 * t8 + 8 * hl;
+        f32x4 d0 = *reinterpret_cast<const f32x4 *>(sDelta + qq);
+        f32x4 d1 = *reinterpret_cast<const f32x4 *>(sDelta + qq + 4);
+        float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const int i = 8 * t8 + e;
+          dsb[i >> 1] = pack_bf16x2(sacc[i] * (pacc[i] - dv[e]), sacc[i + 1] * (pacc[i + 1] - dv[e + 1]));
         }
       }
-    }
+      __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        uint4 raw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
+        bf16x8 bd = *reinterpret_cast<bf16x8 *>(&raw);
+#pragma unroll
+        for (int dm = 0; dm < D / 32; ++dm)
+          kacc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(0, mt, tt, dm), bd, kacc[dm], 0, 0, 0);
+      }
     }
   }
 
@@ -568,8 +497,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
       po[1] = make_uint4(w[4], w[5], w[6], w[7]);
     }
   };
-  emit(gacc, WHAT == 0);
-  if (BOTH) emit(vacc, true);
+  emit(kacc, false);
+  emit(vacc, true);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -618,11 +547,13 @@ static size_t transposed_bytes(const Problem &pb) {
 static size_t order_bytes(const Problem &pb) {
   return round256((size_t)pb.n_slabs * pb.Nb * sizeof(int32_t));
 }
+static size_t rowstat_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.Lpad * sizeof(float));
+}
 size_t bwd_workspace_bytes(const Problem &pb) {
-  // Q^T, K^T, dO^T as [slab][Nb][d][block] bf16, then Delta [slab][L] fp32, then the order of
-  // the dK / dV workgroups
-  return 3 * transposed_bytes(pb) + round256((size_t)pb.n_slabs * pb.L * sizeof(float)) +
-         order_bytes(pb);
+  // K^T as [slab][Nb][d][block] bf16, then three [slab][Lpad] fp32 arrays (Delta, LSE in log2
+  // units, the same minus the pooled keys' bias), then the order of the dK / dV workgroups
+  return transposed_bytes(pb) + 3 * rowstat_bytes(pb) + order_bytes(pb);
 }
 // sum of the per-range partial gradients of the pooled tokens into range 0's buffer
 __global__ void pooled_reduce_kernel(float *buf, int chunks, int64_t n) {
@@ -661,38 +592,20 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 0>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDvLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D, 2>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkvLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
   hipError_t e = hipSuccess;
-  // dK and dV from one kernel (one S and P per tile for both); ASA_BWD_SPLIT_DKV selects the
-  // two single-gradient kernels instead (for A/B timing)
-  static const bool fused = getenv("ASA_BWD_SPLIT_DKV") == nullptr;
   timing_begin(st);
   if (pooled_launch) {
     // gradients of the pooled tokens first (fp32, every query block attends them) ...
     const BwdArgs &g = *pooled_launch;
     const int ggrid = xcd_grid(g.n_slabs * g.Nbk * g.q_chunks);
-    if (fused) {
-      hipLaunchKernelGGL((dkv_kernel<BLK, D, 2>), dim3(ggrid), dim3(C::kThreads), C::kDkvLds, st, g);
-      e = hipGetLastError();
-    } else {
-      hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(ggrid), dim3(C::kThreads), C::kDvLds, st, g);
-      e = hipGetLastError();
-      if (e == hipSuccess) {
-        hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(ggrid), dim3(C::kThreads), C::kDkLds, st, g);
-        e = hipGetLastError();
-      }
-    }
+    hipLaunchKernelGGL((dkv_kernel<BLK, D>), dim3(ggrid), dim3(C::kThreads), C::kDkvLds, st, g);
+    e = hipGetLastError();
     if (e == hipSuccess && g.q_chunks > 1) {
       const int64_t n4 = (int64_t)g.n_slabs * g.Nbk * BLK * D / 4;
       const int rgrid = (int)((n4 + 255) / 256);
@@ -702,16 +615,8 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
     }
   }
   // ... then the tokens' own gradients, which add their share of the pooled ones
-  if (e == hipSuccess && fused) {
-    hipLaunchKernelGGL((dkv_kernel<BLK, D, 2>), dim3(grid), dim3(C::kThreads), C::kDkvLds, st, a);
-    e = hipGetLastError();
-  }
-  if (e == hipSuccess && !fused) {
-    hipLaunchKernelGGL((dkv_kernel<BLK, D, 0>), dim3(grid), dim3(C::kThreads), C::kDvLds, st, a);
-    e = hipGetLastError();
-  }
-  if (e == hipSuccess && !fused) {
-    hipLaunchKernelGGL((dkv_kernel<BLK, D, 1>), dim3(grid), dim3(C::kThreads), C::kDkLds, st, a);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((dkv_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), C::kDkvLds, st, a);
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
@@ -731,34 +636,30 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
                       const int32_t *row_idx, void *dq, void *dk, void *dv, void *workspace,
                       hipStream_t st, const GlobalTokens *gt) {
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
-  const size_t tb = transposed_bytes(pb);
-  bf16 *qt = reinterpret_cast<bf16 *>(ws);
-  bf16 *kt = reinterpret_cast<bf16 *>(ws + tb);
-  bf16 *dot = reinterpret_cast<bf16 *>(ws + 2 * tb);
-  float *delta = reinterpret_cast<float *>(ws + 3 * tb);
-  int32_t *order = reinterpret_cast<int32_t *>(ws + 3 * tb +
-                                               round256((size_t)pb.n_slabs * pb.L * sizeof(float)));
+  const size_t tb = transposed_bytes(pb), rb = rowstat_bytes(pb);
+  bf16 *kt = reinterpret_cast<bf16 *>(ws);
+  float *delta = reinterpret_cast<float *>(ws + tb);
+  float *lse2 = reinterpret_cast<float *>(ws + tb + rb);
+  float *lse2g = reinterpret_cast<float *>(ws + tb + 2 * rb);
+  int32_t *order = reinterpret_cast<int32_t *>(ws + tb + 3 * rb);
 
-  hipError_t e = launch_transpose(pb, q, pb.q, qt, st);
+  hipError_t e = launch_transpose(pb, k, pb.k, kt, st);
   if (e != hipSuccess) return e;
-  e = launch_transpose(pb, k, pb.k, kt, st);
-  if (e != hipSuccess) return e;
-  e = launch_transpose(pb, d_o, pb.o, dot, st);
-  if (e != hipSuccess) return e;
-  dim3 dgrid((pb.L + 15) / 16, pb.n_slabs);
+  const float pooled_bias = gt ? log2f((float)gt->n) : 0.f;
+  dim3 dgrid((pb.Lpad + 15) / 16, pb.n_slabs);
   if (pb.d == 128)
     hipLaunchKernelGGL(delta_kernel<128>, dgrid, dim3(256), 0, st, o, o_lo, d_o, pb.o, pb.H, pb.L,
-                       delta);
+                       pb.Lpad, lse, pooled_bias, delta, lse2, gt ? lse2g : nullptr);
   else
     hipLaunchKernelGGL(delta_kernel<64>, dgrid, dim3(256), 0, st, o, o_lo, d_o, pb.o, pb.H, pb.L,
-                       delta);
+                       pb.Lpad, lse, pooled_bias, delta, lse2, gt ? lse2g : nullptr);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   BwdArgs a;
   a.q = q; a.k = k; a.v = v; a.d_o = d_o;
-  a.qt = qt; a.kt = kt; a.dot = dot;
-  a.lse = lse; a.delta = delta;
+  a.kt = kt;
+  a.lse2 = lse2; a.delta = delta;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.col_ptr = col_ptr; a.row_idx = row_idx;
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.tq = pb.q; a.tk = pb.k; a.tv = pb.v; a.to = pb.o;
@@ -775,7 +676,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
       a.order = order;
     }
   }
-  a.Lk = pb.L; a.Nbk = pb.Nb; a.key_bias_log2 = 0.f;
+  a.Lk = pb.L; a.Nbk = pb.Nb;
   a.gk32 = a.gv32 = nullptr; a.q_chunks = 1; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
   a.kg = a.vg = nullptr; a.kgt = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
   BwdArgs g;                       // the launch whose key side is the pooled tokens
@@ -793,12 +694,12 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     tvg.sL = pb.d; tvg.sH = (int64_t)pg.Lpad * pb.d; tvg.sB = tvg.sH * pb.H;
     e = launch_transpose(pg, gt->kg, tvg, kgt, st);
     if (e != hipSuccess) return e;
-    const float bias = log2f((float)gt->n);
+    const float bias = pooled_bias;
     g = a;
     g.order = nullptr;
     g.k = gt->kg; g.v = gt->vg; g.tk = tvg; g.tv = tvg;
     g.col_ptr = nullptr; g.row_idx = nullptr;          // every query block attends the pooled tokens
-    g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.key_bias_log2 = bias;
+    g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.lse2 = lse2g;
     g.gk32 = gk32; g.gv32 = gv32; g.q_chunks = chunks;
     pooled = &g;
     a.pool_gk = gk32; a.pool_gv = gv32; a.pool_n = gt->n; a.pool_rows = gt->Nbg * pb.block;

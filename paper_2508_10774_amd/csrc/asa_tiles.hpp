@@ -74,6 +74,13 @@ __device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
 #endif
 }
 
+// 4 bytes per lane: the wavefront's 64 values land contiguously (256 bytes).
+__device__ __forceinline__ void lds_dma4(const void *src, void *lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, (lds_void *)lds_dst, 4, 0, 0);
+#endif
+}
+
 // The same load with the address split into a wave-uniform 64-bit base (scalar registers) and
 // a 32-bit per-lane byte offset: stepping to another tile then costs scalar adds only and the
 // per-lane offsets stay 32 bits wide.  The compiler does not see this load: the caller waits
@@ -255,24 +262,6 @@ struct LeanRowTileCopy {
         const int src_row = row > lim ? lim : row;                        // may be negative
         lds_dma16(base + (int64_t)src_row * pitch + (pos ^ sw) * 16, stage + (wave * kInstr + i) * 512);
       }
-    }
-  }
-};
-
-template <int BLK, int D, int WAVES>
-struct LeanColTileCopy {
-  static constexpr int kInstr = D * 8 / 64 / WAVES;
-  // columns [col0, col0 + 64) of the transposed tile `tile` ([D][BLK] bf16) into `stage`
-  static __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tile, int col0, int wave,
-                                               int lane) {
-    const char *base = reinterpret_cast<const char *>(tile + col0);
-    const int l8 = lane / 8, pos = lane % 8;
-#pragma unroll
-    for (int i = 0; i < kInstr; ++i) {
-      const int r0 = (wave * kInstr + i) * 8;                             // wave-uniform
-      const int sw = v_swz(r0 + l8);
-      const uint32_t lo = (uint32_t)((l8 * BLK + ((pos ^ sw) * 8)) * 2);
-      lds_dma16(base + (int64_t)r0 * BLK * 2 + lo, stage + (wave * kInstr + i) * 512);
     }
   }
 };
