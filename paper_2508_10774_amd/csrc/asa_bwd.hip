@@ -10,7 +10,7 @@
 // Operand orientation (32x32x16 bf16 MFMA, see asa_fwd.hip for kappa / rho):
 //   dq_kernel : keys on the M axis, queries on lanes: S^T = K Q^T and dP^T = V dO^T share the
 //               accumulator layout, LSE and Delta are per-lane scalars, and bf16(dS^T) is directly
-//               the B operand of dQ^T = K^T dS^T (K^T tiles come from a per-block transposed copy of K).
+//               the B operand of dQ^T = K^T dS^T (K^T operand by transposing LDS reads of the K rows).
 //   dkv_kernel: queries on the M axis, keys on lanes: S = Q K^T, dP = dO V^T with K, V of the
 //               wave's 32 keys resident in registers; bf16(P) and bf16(dS) are the B operands of
 //               dV^T = dO^T P and dK^T = Q^T dS (dO^T, Q^T operands by transposing LDS reads of
@@ -25,7 +25,6 @@
 namespace asa {
 
 __device__ __forceinline__ int kappa_b(int r) { return kappa(r); }
-__device__ __forceinline__ int rho_b(int r) { return rho(r); }
 
 constexpr float kLog2e = 1.44269504088896340736f;
 
@@ -79,7 +78,6 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *o, const void *o
 
 struct BwdArgs {
   const void *q, *k, *v, *d_o;
-  const bf16 *kt;             // [slab][Nb][d][block] transposed-tile copy of K (dQ kernel)
   const float *lse2, *delta;  // [slab][Lpad]: LSE * log2(e) (minus this launch's key bias), Delta; padded with +inf, 0
   const int32_t *row_ptr, *col_idx, *col_ptr, *row_idx;
   void *dq, *dk, *dv;
@@ -96,7 +94,6 @@ struct BwdArgs {
   int pool_n, pool_rows;  // pooling window; rows per slab of pool_gk / pool_gv
   // dQ kernel: pooled tiles appended to every query block's list
   const void *kg, *vg;    // [slab][Nbg * block][d] bf16
-  const bf16 *kgt;        // [slab][Nbg][d][block]
   int Lg, Nbg;
   float pooled_bias_log2;
 };
@@ -108,26 +105,26 @@ struct BwdCfg {
   static constexpr int kST = 64;                 // rows (keys or queries) per step
   static constexpr int kSub = BLK / kST;         // steps per block
   static constexpr int kRowTile = kST * D;       // [64][D]  elements, swizzled, unpadded
-  static constexpr int kColTile = D * kST;       // [D][64]
-  static constexpr int kDqLds = (2 * kRowTile + kColTile) * 2;
+  static constexpr int kDqStage = 2 * kRowTile * 2;                  // K rows, V rows
+  static constexpr int kDqLds = 2 * kDqStage;
   static constexpr int kDkvStage = 2 * kRowTile * 2 + 2 * kST * 4;   // Q rows, dO rows, LSE, Delta
   static constexpr int kDkvLds = 2 * kDkvStage;
 };
 
 // ---------------------------------------------------------------------------------------
-// dQ: one workgroup per query block, one wavefront per 32 query rows.  Per step of 64 keys the
-// workgroup copies K rows, V rows and the matching K^T slice straight into LDS; two
-// workgroups share a CU, so one computes while the other's copies are in flight.
+// dQ: one workgroup per query block, one wavefront per 32 query rows (its Q and dO rows stay
+// in registers as B operands).  Per step of 64 keys the workgroup copies K rows and V rows
+// straight into one of two LDS stages while it works on the other; the "channels x keys"
+// operand of dQ^T = K^T dS^T is gathered from the K row tile by the transposing LDS read.
 // ---------------------------------------------------------------------------------------
 // GT: with the pooled (global) tokens of ASA_G appended to every query block's list
 template <int BLK, int D, bool GT>
 __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   using C = BwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
-  bf16 *Ks = reinterpret_cast<bf16 *>(smem);
-  bf16 *Vs = Ks + C::kRowTile;
-  bf16 *Kt = Vs + C::kRowTile;
   __shared__ int cols[kMaxNb];
+  constexpr int kStage = C::kDqStage;          // K rows [64][D], V rows [64][D] (t_swz images)
+  constexpr int kVOff = C::kRowTile * 2;
 
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
@@ -141,7 +138,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   const bf16 *ks = slab_ptr(a.k, a.tk, slab, a.H);
   const bf16 *vs = slab_ptr(a.v, a.tv, slab, a.H);
   const bf16 *gs = slab_ptr(a.d_o, a.to, slab, a.H);
-  const bf16 *kts = a.kt + (int64_t)slab * D * a.Lpad;
   const bool dense = a.row_ptr == nullptr;   // no index lists: every key block
   const int t_begin = dense ? 0 : a.row_ptr[slab * (a.Nb + 1) + qb];
   const int n_own_tiles = dense ? a.Nb : a.row_ptr[slab * (a.Nb + 1) + qb + 1] - t_begin;
@@ -151,10 +147,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     for (int t = tid; t < n_tiles; t += C::kThreads)
       cols[t] = t >= n_own_tiles ? t - n_own_tiles : (dense ? t : g[t]);
   }
-  // pooled keys / values of this slab: rows of D elements, transposed tiles like K^T's
+  // pooled keys / values of this slab: rows of D elements, padded to whole blocks
   const bf16 *kgs = reinterpret_cast<const bf16 *>(a.kg) + (int64_t)slab * a.Nbg * BLK * D;
   const bf16 *vgs = reinterpret_cast<const bf16 *>(a.vg) + (int64_t)slab * a.Nbg * BLK * D;
-  const bf16 *kgts = a.kgt + (int64_t)slab * a.Nbg * D * BLK;
 
   const int qrow = qb * BLK + wave * 32 + n;
   const bool qvalid = qrow < a.L;
@@ -175,40 +170,45 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[dm][i] = 0.f;
 
-  RowTileCopy<C::kST, D, C::kWaves> copy_k, copy_v;
-  ColTileCopy<BLK, D, C::kWaves> copy_kt;
-  copy_k.init(wave, lane, a.tk.sL);
-  copy_v.init(wave, lane, a.tv.sL);
-  copy_kt.init(wave, lane);
-  RowTileCopy<C::kST, D, C::kWaves> copy_pooled;   // rows of the pooled tensors (pitch D)
-  if (GT) copy_pooled.init(wave, lane, D);
-
-  // A fragments: rows kappa(n) of a 32-key group (K, V), rows rho(n) of a 32-channel group (K^T)
-  const int kr = kappa_b(n), cr = rho_b(n);
-  const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
+  // row-wise A fragments (S^T = K Q^T, dP^T = V dO^T): row kappa(n) of a 32-key group
+  const int kr = kappa_b(n);
+  const int kx = (hl ^ t_swz<D>(kr)) * 8;
+  // transposed A fragments "32 channels x 16 keys" of dQ^T += K^T dS^T (see dkv_kernel)
+  const lds_char *smem_lds = (const lds_char *)smem;
+  const int tr_i = lane & 15, tr_w = tr_i & 3, tr_j = tr_i >> 2, tr_b = (lane >> 4) & 1;
+  const uint32_t tr_lane = tr_piece<D>(8 * hl + tr_j, 16 * (tr_w & 1) + 8 * tr_b + 4 * (tr_w >> 1));
   const float c = a.scale_log2e;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_steps = n_tiles * C::kSub;
+  auto issue = [&](int step, int stage) {
+    const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kST;
+    int lane_o = lane;
+    asm volatile("" : "+v"(lane_o));   // offsets are rebuilt here, not hoisted into registers
+    using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
+    unsigned char *st = smem + stage * kStage;
+    if (GT && step >= n_own_tiles * C::kSub) {
+      RowCopy::issue(reinterpret_cast<bf16 *>(st), kgs, key0, a.Nbg * BLK, D, wave, lane_o);   // never ragged
+      RowCopy::issue(reinterpret_cast<bf16 *>(st + kVOff), vgs, key0, a.Nbg * BLK, D, wave, lane_o);
+    } else {
+      RowCopy::issue(reinterpret_cast<bf16 *>(st), ks, key0, a.L, a.tk.sL, wave, lane_o);
+      RowCopy::issue(reinterpret_cast<bf16 *>(st + kVOff), vs, key0, a.L, a.tv.sL, wave, lane_o);
+    }
+  };
+  __syncthreads();   // cols[] is written
+  if (n_steps > 0) issue(0, 0);
   for (int step = 0; step < n_steps; ++step) {
     __builtin_amdgcn_s_setprio(3);
-    __syncthreads();   // the previous step's fragments are consumed (and cols[] is written)
-    const int j = cols[step / C::kSub];
-    const int sub = step % C::kSub;
-    const int key0 = j * BLK + sub * C::kST;
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): my copies of this step have landed
+    __syncthreads();                      // everyone's have; everyone is done with the other stage
+    const int stage = step & 1;
+    if (step + 1 < n_steps) issue(step + 1, stage ^ 1);
+    const bf16 *Ks = reinterpret_cast<const bf16 *>(smem + stage * kStage);
+    const bf16 *Vs = Ks + C::kRowTile;
+    const uint32_t tr_base = tr_lane + (uint32_t)(stage * kStage);   // kStage % 512 == 0
+    const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kST;
     const bool pooled = GT && step >= n_own_tiles * C::kSub;
-    if (pooled) {
-      copy_pooled.issue(Ks, kgs, key0, a.Nbg * BLK);   // padded to whole blocks: never ragged
-      copy_pooled.issue(Vs, vgs, key0, a.Nbg * BLK);
-      copy_kt.issue(Kt, kgts + (int64_t)j * D * BLK, sub * C::kST);
-    } else {
-      copy_k.issue(Ks, ks, key0, a.L);
-      copy_v.issue(Vs, vs, key0, a.L);
-      copy_kt.issue(Kt, kts + (int64_t)j * D * BLK, sub * C::kST);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
     const int key_end = pooled ? a.Lg : a.L;   // keys at or past it do not exist
     const bool tail = key0 + C::kST > key_end;
     const float lse_b = pooled ? lse2 - a.pooled_bias_log2 : lse2;
@@ -225,6 +225,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
         bf16x8 va = *reinterpret_cast<const bf16x8 *>(vrow + ((16 * s) ^ kx));
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[s], pacc, 0, 0, 0);
       }
+      // accumulator register i of lane half hl is key 32mt + 16(i/8) + 8hl + (i%8)
       uint32_t dsb[8];
       __builtin_amdgcn_s_setprio(3);   // vector work goes ahead of the other workgroup's MFMA stream
 #pragma unroll
@@ -245,8 +246,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
         bf16x8 dsf = *reinterpret_cast<bf16x8 *>(&raw);
 #pragma unroll
         for (int dm = 0; dm < D / 32; ++dm) {
-          bf16x8 ta = *reinterpret_cast<const bf16x8 *>(Kt + (dm * 32 + cr) * C::kST +
-                                                        ((16 * (2 * mt + tt)) ^ cx));
+          // keys 32 mt + 16 tt + 8 hl + (0..7) of channels 32 dm + rho(lane % 32)
+          const uint32_t x0 = (uint32_t)(((4 * dm) ^ t_swz<D>(0)) * 16), x1 = (uint32_t)(((4 * dm) ^ t_swz<D>(4)) * 16);
+          const bf16x4 lo = lds_read_tr16(smem_lds + ((tr_base ^ x0) + (uint32_t)((32 * mt + 16 * tt) * D * 2)));
+          const bf16x4 hi = lds_read_tr16(smem_lds + ((tr_base ^ x1) + (uint32_t)((32 * mt + 16 * tt + 4) * D * 2)));
+          const bf16x8 ta = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           acc[dm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, dsf, acc[dm], 0, 0, 0);
         }
       }
@@ -540,10 +544,6 @@ __global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t *col_ptr,
 }
 
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
-static size_t transposed_bytes(const Problem &pb) {
-  return round256((size_t)pb.n_slabs * pb.d * pb.Lpad * sizeof(uint16_t));
-}
-
 static size_t order_bytes(const Problem &pb) {
   return round256((size_t)pb.n_slabs * pb.Nb * sizeof(int32_t));
 }
@@ -551,9 +551,9 @@ static size_t rowstat_bytes(const Problem &pb) {
   return round256((size_t)pb.n_slabs * pb.Lpad * sizeof(float));
 }
 size_t bwd_workspace_bytes(const Problem &pb) {
-  // K^T as [slab][Nb][d][block] bf16, then three [slab][Lpad] fp32 arrays (Delta, LSE in log2
-  // units, the same minus the pooled keys' bias), then the order of the dK / dV workgroups
-  return transposed_bytes(pb) + 3 * rowstat_bytes(pb) + order_bytes(pb);
+  // three [slab][Lpad] fp32 arrays (Delta, LSE in log2 units, the same minus the pooled keys'
+  // bias), then the order of the dK / dV workgroups
+  return 3 * rowstat_bytes(pb) + order_bytes(pb);
 }
 // sum of the per-range partial gradients of the pooled tokens into range 0's buffer
 __global__ void pooled_reduce_kernel(float *buf, int chunks, int64_t n) {
@@ -576,9 +576,8 @@ static size_t pooled_rows_bytes(const Problem &pb, int Nbg, size_t elem) {
   return round256((size_t)pb.n_slabs * Nbg * pb.block * pb.d * elem);
 }
 size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg) {
-  // ... then the pooled keys' transposed tiles (bf16) and the pooled tokens' dK, dV (fp32)
-  return bwd_workspace_bytes(pb) + pooled_rows_bytes(pb, Nbg, 2) +
-         2 * pooled_chunks(pb, Nbg) * pooled_rows_bytes(pb, Nbg, 4);
+  // ... then the pooled tokens' dK, dV (fp32, one buffer per range of query blocks)
+  return bwd_workspace_bytes(pb) + 2 * pooled_chunks(pb, Nbg) * pooled_rows_bytes(pb, Nbg, 4);
 }
 
 template <int BLK, int D>
@@ -636,15 +635,13 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
                       const int32_t *row_idx, void *dq, void *dk, void *dv, void *workspace,
                       hipStream_t st, const GlobalTokens *gt) {
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
-  const size_t tb = transposed_bytes(pb), rb = rowstat_bytes(pb);
-  bf16 *kt = reinterpret_cast<bf16 *>(ws);
-  float *delta = reinterpret_cast<float *>(ws + tb);
-  float *lse2 = reinterpret_cast<float *>(ws + tb + rb);
-  float *lse2g = reinterpret_cast<float *>(ws + tb + 2 * rb);
-  int32_t *order = reinterpret_cast<int32_t *>(ws + tb + 3 * rb);
+  const size_t rb = rowstat_bytes(pb);
+  float *delta = reinterpret_cast<float *>(ws);
+  float *lse2 = reinterpret_cast<float *>(ws + rb);
+  float *lse2g = reinterpret_cast<float *>(ws + 2 * rb);
+  int32_t *order = reinterpret_cast<int32_t *>(ws + 3 * rb);
 
-  hipError_t e = launch_transpose(pb, k, pb.k, kt, st);
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
   const float pooled_bias = gt ? log2f((float)gt->n) : 0.f;
   dim3 dgrid((pb.Lpad + 15) / 16, pb.n_slabs);
   if (pb.d == 128)
@@ -658,7 +655,6 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
 
   BwdArgs a;
   a.q = q; a.k = k; a.v = v; a.d_o = d_o;
-  a.kt = kt;
   a.lse2 = lse2; a.delta = delta;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.col_ptr = col_ptr; a.row_idx = row_idx;
   a.dq = dq; a.dk = dk; a.dv = dv;
@@ -678,22 +674,16 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   }
   a.Lk = pb.L; a.Nbk = pb.Nb;
   a.gk32 = a.gv32 = nullptr; a.q_chunks = 1; a.pool_gk = a.pool_gv = nullptr; a.pool_n = 1; a.pool_rows = 0;
-  a.kg = a.vg = nullptr; a.kgt = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
+  a.kg = a.vg = nullptr; a.Lg = a.Nbg = 0; a.pooled_bias_log2 = 0.f;
   BwdArgs g;                       // the launch whose key side is the pooled tokens
   const BwdArgs *pooled = nullptr;
   if (gt) {
     unsigned char *wg = ws + bwd_workspace_bytes(pb);
-    bf16 *kgt = reinterpret_cast<bf16 *>(wg);
-    float *gk32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2));
+    float *gk32 = reinterpret_cast<float *>(wg);
     const int chunks = pooled_chunks(pb, gt->Nbg);
-    float *gv32 = reinterpret_cast<float *>(wg + pooled_rows_bytes(pb, gt->Nbg, 2) +
-                                            chunks * pooled_rows_bytes(pb, gt->Nbg, 4));
-    Problem pg = pb;               // the pooled tensors as a problem of their own
-    pg.L = gt->Lg; pg.Nb = gt->Nbg; pg.Lpad = gt->Nbg * pb.block;
-    TensorView tvg;
-    tvg.sL = pb.d; tvg.sH = (int64_t)pg.Lpad * pb.d; tvg.sB = tvg.sH * pb.H;
-    e = launch_transpose(pg, gt->kg, tvg, kgt, st);
-    if (e != hipSuccess) return e;
+    float *gv32 = reinterpret_cast<float *>(wg + chunks * pooled_rows_bytes(pb, gt->Nbg, 4));
+    TensorView tvg;                // the pooled tensors: [slab][Nbg * block][d], rows of d elements
+    tvg.sL = pb.d; tvg.sH = (int64_t)gt->Nbg * pb.block * pb.d; tvg.sB = tvg.sH * pb.H;
     const float bias = pooled_bias;
     g = a;
     g.order = nullptr;
@@ -703,7 +693,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     g.gk32 = gk32; g.gv32 = gv32; g.q_chunks = chunks;
     pooled = &g;
     a.pool_gk = gk32; a.pool_gv = gv32; a.pool_n = gt->n; a.pool_rows = gt->Nbg * pb.block;
-    a.kg = gt->kg; a.vg = gt->vg; a.kgt = kgt; a.Lg = gt->Lg; a.Nbg = gt->Nbg;
+    a.kg = gt->kg; a.vg = gt->vg; a.Lg = gt->Lg; a.Nbg = gt->Nbg;
     a.pooled_bias_log2 = bias;
   }
   if (pb.block == 128 && pb.d == 128) return launch_bwd_t<128, 128>(a, pooled, st);
