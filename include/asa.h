@@ -63,7 +63,9 @@ typedef struct asa_params {
   float scale;                   /* soft-max scale; 0 selects 1/sqrt(d)                      */
   /* Element strides of the B, H and L axes; d has stride 1.  All zero selects the packed
      layout {H*L*d, L*d, d}.  q_stride also applies to dQ, k_stride to dK, v_stride to dV,
-     o_stride to dO.  Strides must be multiples of 8 elements (16-byte rows).               */
+     o_stride to dO.  Strides must be multiples of 8 elements (16-byte rows); the L stride
+     must be below 2^24 elements (the kernels address the 64 rows of a tile with 32-bit
+     byte offsets).  Anything else: ASA_ERR_INVALID_ARG.                                     */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
 } asa_params;
 

@@ -34,6 +34,7 @@ static bool view_from(const int64_t st[3], const Problem &pb, TensorView *tv) {
   }
   if (st[2] < pb.d || st[0] < 0 || st[1] < 0) return false;
   if ((st[0] % 8) || (st[1] % 8) || (st[2] % 8)) return false;  // rows are read 16 bytes at a time
+  if (st[2] >= ((int64_t)1 << 24)) return false;  // 64 rows of a tile within 32-bit byte offsets
   tv->sB = st[0];
   tv->sH = st[1];
   tv->sL = st[2];

@@ -62,7 +62,7 @@ def test_argument_errors_are_reported_without_a_gpu():
                           fake, fake, fake, None, fake, fake, fake, fake, 1 << 30, None) == -1
     for bad in (dict(k_samples=0), dict(k_samples=65), dict(sample_offsets=[3, 1] + list(range(4, 18))),
                 dict(r_min=0.6, r_max=0.5), dict(tau=float("nan")), dict(n_prefix_dense=-1),
-                dict(q_stride=(0, 0, 60))):
+                dict(q_stride=(0, 0, 60)), dict(k_stride=(1 << 40, 1 << 36, 1 << 24))):
         kw = dict(B=1, H=2, L=1024, d=64, block=64)
         kw.update(bad)
         pb = binding.Params(**kw)
