@@ -175,6 +175,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   const int kx = (hl ^ t_swz<D>(kr)) * 8;
   // transposed A fragments "32 channels x 16 keys" of dQ^T += K^T dS^T (see dkv_kernel)
   const lds_char *smem_lds = (const lds_char *)smem;
+  const uint32_t smem_addr = ASA_LDS_ADDR_OF(smem);
   const int tr_i = lane & 15, tr_w = tr_i & 3, tr_j = tr_i >> 2, tr_b = (lane >> 4) & 1;
   const uint32_t tr_lane = tr_piece<D>(8 * hl + tr_j, 16 * (tr_w & 1) + 8 * tr_b + 4 * (tr_w >> 1));
   const float c = a.scale_log2e;
@@ -187,13 +188,13 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     int lane_o = lane;
     asm volatile("" : "+v"(lane_o));   // offsets are rebuilt here, not hoisted into registers
     using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
-    unsigned char *st = smem + stage * kStage;
+    const uint32_t st = smem_addr + stage * kStage;
     if (GT && step >= n_own_tiles * C::kSub) {
-      RowCopy::issue(reinterpret_cast<bf16 *>(st), kgs, key0, a.Nbg * BLK, D, wave, lane_o);   // never ragged
-      RowCopy::issue(reinterpret_cast<bf16 *>(st + kVOff), vgs, key0, a.Nbg * BLK, D, wave, lane_o);
+      RowCopy::issue(st, kgs, key0, a.Nbg * BLK, D, wave, lane_o);   // never ragged
+      RowCopy::issue(st + kVOff, vgs, key0, a.Nbg * BLK, D, wave, lane_o);
     } else {
-      RowCopy::issue(reinterpret_cast<bf16 *>(st), ks, key0, a.L, a.tk.sL, wave, lane_o);
-      RowCopy::issue(reinterpret_cast<bf16 *>(st + kVOff), vs, key0, a.L, a.tv.sL, wave, lane_o);
+      RowCopy::issue(st, ks, key0, a.L, a.tk.sL, wave, lane_o);
+      RowCopy::issue(st + kVOff, vs, key0, a.L, a.tv.sL, wave, lane_o);
     }
   };
   __syncthreads();   // cols[] is written
@@ -340,6 +341,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   // a 16-lane group addresses query i / 4 of 4 consecutive ones and 4 of the channels that
   // the MFMA rows of its group stand for (row order rho); two reads make the 8 queries of a lane
   const lds_char *smem_lds = (const lds_char *)smem;
+  const uint32_t smem_addr = ASA_LDS_ADDR_OF(smem);
   const int tr_i = lane & 15, tr_w = tr_i & 3, tr_j = tr_i >> 2, tr_b = (lane >> 4) & 1;
   const uint32_t tr_lane = tr_piece<D>(8 * hl + tr_j, 16 * (tr_w & 1) + 8 * tr_b + 4 * (tr_w >> 1));
   const float c = a.scale_log2e;
@@ -352,11 +354,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     int lane_o = lane;
     asm volatile("" : "+v"(lane_o));   // offsets are rebuilt here, not hoisted into registers
     using RowCopy = LeanRowTileCopy<C::kST, D, C::kWaves>;
-    unsigned char *st = smem + stage * kStage;
-    RowCopy::issue(reinterpret_cast<bf16 *>(st), qs, q0, a.L, a.tq.sL, wave, lane_o);
-    RowCopy::issue(reinterpret_cast<bf16 *>(st + kGOff), gs, q0, a.L, a.to.sL, wave, lane_o);
-    if (wave == 0) lds_dma4(lse_s + q0 + lane_o, st + kLseOff);
-    if (wave == 1) lds_dma4(delta_s + q0 + lane_o, st + kDeltaOff);
+    const uint32_t st = smem_addr + stage * kStage;
+    RowCopy::issue(st, qs, q0, a.L, a.tq.sL, wave, lane_o);
+    RowCopy::issue(st + kGOff, gs, q0, a.L, a.to.sL, wave, lane_o);
+    if (wave == 0) lds_dma4_v(lse_s + q0 + lane_o, st + kLseOff);
+    if (wave == 1) lds_dma4_v(delta_s + q0 + lane_o, st + kDeltaOff);
   };
   __syncthreads();   // rows[] is written
   if (n_steps > 0) issue(0, 0);

@@ -74,13 +74,6 @@ __device__ __forceinline__ void lds_dma16(const void *src, void *lds_dst) {
 #endif
 }
 
-// 4 bytes per lane: the wavefront's 64 values land contiguously (256 bytes).
-__device__ __forceinline__ void lds_dma4(const void *src, void *lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds(src, (lds_void *)lds_dst, 4, 0, 0);
-#endif
-}
-
 // The same load with the address split into a wave-uniform 64-bit base (scalar registers) and
 // a 32-bit per-lane byte offset: stepping to another tile then costs scalar adds only and the
 // per-lane offsets stay 32 bits wide.  The compiler does not see this load: the caller waits
@@ -107,6 +100,19 @@ __device__ __forceinline__ void lds_dma16_sv(const void *uniform_base, uint32_t 
                       ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(lane_off), "s"(bu), "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
+#endif
+}
+// The same (compiler-invisible) load with a full per-lane 64-bit address, and its 4-byte form.
+__device__ __forceinline__ void lds_dma16_v(const void *lane_ptr, uint32_t lds_byte_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(lane_ptr), "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
+#endif
+}
+__device__ __forceinline__ void lds_dma4_v(const void *lane_ptr, uint32_t lds_byte_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(lane_ptr), "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
 #endif
 }
 // LDS byte address of an object that the compiler knows to live in LDS (apply it to the
@@ -237,9 +243,10 @@ struct LeanRowTileCopy {
   static constexpr int kInstr = ROWS * kChunks / 64 / WAVES;  // wave instructions per copy
   static_assert((kInstr * kRowsPer) % 16 == 0, "a wave's first row must be a multiple of 16");
 
-  // copy rows [row0, row0 + ROWS) of `tensor` (slab base, row pitch sL elements) into `stage`;
-  // rows past L - 1 re-read row L - 1
-  static __device__ __forceinline__ void issue(bf16 *stage, const bf16 *tensor, int row0, int L,
+  // copy rows [row0, row0 + ROWS) of `tensor` (slab base, row pitch sL elements) to the LDS
+  // byte address `stage`; rows past L - 1 re-read row L - 1.  The loads are of the kind the
+  // compiler does not see: the caller waits with an explicit vmcnt before reading the tile.
+  static __device__ __forceinline__ void issue(uint32_t stage, const bf16 *tensor, int row0, int L,
                                                int64_t sL, int wave, int lane) {
     const int64_t pitch = sL * 2;
     const int lane_row = lane / kChunks, pos = lane % kChunks;
@@ -252,7 +259,7 @@ struct LeanRowTileCopy {
         const int r0 = (wave * kInstr + i) * kRowsPer;                    // wave-uniform
         const int sw = t_swz<D>(((i * kRowsPer) & 15) + lane_row);        // = t_swz(r0 + lane_row)
         const uint32_t lo = lane_row_off + (uint32_t)((pos ^ sw) * 16);
-        lds_dma16(base + (int64_t)r0 * pitch + lo, stage + (wave * kInstr + i) * 512);
+        lds_dma16_sv(base + (int64_t)r0 * pitch, lo, stage + (wave * kInstr + i) * 1024);
       }
     } else {
 #pragma unroll
@@ -260,7 +267,7 @@ struct LeanRowTileCopy {
         const int row = (wave * kInstr + i) * kRowsPer + lane_row;
         const int sw = t_swz<D>(row);
         const int src_row = row > lim ? lim : row;                        // may be negative
-        lds_dma16(base + (int64_t)src_row * pitch + (pos ^ sw) * 16, stage + (wave * kInstr + i) * 512);
+        lds_dma16_v(base + (int64_t)src_row * pitch + (pos ^ sw) * 16, stage + (wave * kInstr + i) * 1024);
       }
     }
   }
