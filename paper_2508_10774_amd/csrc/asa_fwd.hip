@@ -128,6 +128,10 @@ struct FwdCfg {
   static constexpr int kSub = BLK / kKT;           // steps per key block
   static constexpr int kKElems = kKT * D;          // one K stage:   [64 keys][D]  (unpadded)
   static constexpr int kVElems = D * kKT;          // one V^T stage: [D][64 keys]  (unpadded)
+  // LDS stages of the lock-step kernel: two where the second does not cost a resident workgroup
+  // (block 128: registers allow 2-3 workgroups per CU anyway), one at block 64 (measured at
+  // block 64 / d 64: two stages 1.43 ms, one 1.29 ms; at block 128 / d 128: 1.695 vs 1.73 ms)
+  static constexpr int kStages = BLK == 128 ? 2 : 1;
 };
 
 // The running maximum (and with it O and the row sum) is rescaled only on steps where some row
@@ -135,10 +139,10 @@ struct FwdCfg {
 // The maximum is never allowed to lag behind: a row dominated by one key then has that key's
 // probability equal to exactly 1, free of bf16 rounding, which the backward's Delta relies on.
 //
-// Single-stage kernel: one workgroup per query block, all wavefronts in lock step, one LDS stage
-// (32 KB at d = 128); the copies of a step are waited for right away and the second workgroup
-// on the CU computes meanwhile.  (A two-stage variant that requested the next step's tiles
-// before computing the current one was measured and was slower.)  It serves tensors that the
+// Lock-step kernel: one workgroup per query block, all wavefronts in lock step.  With two LDS
+// stages (2 x 32 KB at d = 128) the copies of step s + 1 are requested right after the barrier
+// that opens step s; with one, the copies of a step are waited for right away and the other
+// workgroups on the CU compute meanwhile.  It serves the tile shapes other than block 128 / d 128 and tensors that the
 // ping-pong kernel below does not take (slabs of 4 GiB and more).
 template <int BLK, int D>
 __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
@@ -191,19 +195,35 @@ __global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_steps = n_tiles * C::kSub;
-  auto fetch = [&](int step) __attribute__((always_inline)) {
+  constexpr int kStageElems = C::kKElems + C::kVElems;
+  const uint32_t lds_addr = ASA_LDS_ADDR_OF(smem);
+  // copies of one step into one of the two stages, issued in the form the compiler does not
+  // track (it would otherwise wait for them before the next LDS read of the other stage)
+  auto fetch = [&](int step, int stage) __attribute__((always_inline)) {
     const int j = cols[step / C::kSub];
     const int sub = step % C::kSub;
-    bf16 *Kd = lds;
-    copy_k.issue(Kd, ks, j * BLK + sub * C::kKT, a.L);
-    copy_v.issue(Kd + C::kKElems, vts + (int64_t)j * D * BLK, sub * C::kKT);
+    const int row0 = j * BLK + sub * C::kKT;
+    const uint32_t st = lds_addr + stage * kStageElems * 2;
+    const char *kbase = reinterpret_cast<const char *>(ks) + (int64_t)row0 * a.tk.sL * 2;
+    const int lim = a.L - 1 - row0;
+    if (lim >= C::kKT - 1) copy_k.issue_at(st, kbase);
+    else copy_k.issue_at_ragged(st, kbase, lim);
+    copy_v.issue_at(st + C::kKElems * 2,
+                    reinterpret_cast<const char *>(vts + (int64_t)j * D * BLK + sub * C::kKT));
   };
+  if (C::kStages == 2) {
+    __syncthreads();                      // cols[] is complete
+    if (n_steps > 0) fetch(0, 0);
+  }
   for (int step = 0; step < n_steps; ++step) {
-    __syncthreads();                      // cols[] is complete; the stage is free again
-    fetch(step);
+    if (C::kStages == 1) {
+      __syncthreads();                    // cols[] is complete; the stage is free again
+      fetch(step, 0);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // my copies of this step have landed
-    __syncthreads();                      // everyone's have
-    const bf16 *Ks = lds;
+    __syncthreads();                      // everyone's have; everyone is done with the other stage
+    if (C::kStages == 2 && step + 1 < n_steps) fetch(step + 1, (step + 1) & 1);
+    const bf16 *Ks = lds + (C::kStages == 2 ? (step & 1) : 0) * kStageElems;
     const bf16 *Vs = Ks + C::kKElems;
     const int key0 = cols[step / C::kSub] * BLK + (step % C::kSub) * C::kKT;
     f32x16 sacc[C::kKT / 32];
@@ -819,7 +839,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
 template <int BLK, int D>
 static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   using C = FwdCfg<BLK, D>;
-  constexpr int lds = (C::kKElems + C::kVElems) * 2;   // one stage
+  constexpr int lds = C::kStages * (C::kKElems + C::kVElems) * 2;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D>),
