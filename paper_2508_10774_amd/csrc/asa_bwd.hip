@@ -105,10 +105,12 @@ struct BwdCfg {
   static constexpr int kST = 64;                 // rows (keys or queries) per step
   static constexpr int kSub = BLK / kST;         // steps per block
   static constexpr int kRowTile = kST * D;       // [64][D]  elements, swizzled, unpadded
+  // LDS stages: two where the second does not cost a resident workgroup (block 128), else one
+  static constexpr int kStages = BLK == 128 ? 2 : 1;
   static constexpr int kDqStage = 2 * kRowTile * 2;                  // K rows, V rows
-  static constexpr int kDqLds = 2 * kDqStage;
+  static constexpr int kDqLds = kStages * kDqStage;
   static constexpr int kDkvStage = 2 * kRowTile * 2 + 2 * kST * 4;   // Q rows, dO rows, LSE, Delta
-  static constexpr int kDkvLds = 2 * kDkvStage;
+  static constexpr int kDkvLds = kStages * kDkvStage;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -197,14 +199,20 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
       RowCopy::issue(st + kVOff, vs, key0, a.L, a.tv.sL, wave, lane_o);
     }
   };
-  __syncthreads();   // cols[] is written
-  if (n_steps > 0) issue(0, 0);
+  if (C::kStages == 2) {
+    __syncthreads();   // cols[] is written
+    if (n_steps > 0) issue(0, 0);
+  }
   for (int step = 0; step < n_steps; ++step) {
     __builtin_amdgcn_s_setprio(3);
+    if (C::kStages == 1) {
+      __syncthreads();                    // cols[] is written; everyone is done with the stage
+      issue(step, 0);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): my copies of this step have landed
     __syncthreads();                      // everyone's have; everyone is done with the other stage
-    const int stage = step & 1;
-    if (step + 1 < n_steps) issue(step + 1, stage ^ 1);
+    const int stage = C::kStages == 2 ? (step & 1) : 0;
+    if (C::kStages == 2 && step + 1 < n_steps) issue(step + 1, stage ^ 1);
     const bf16 *Ks = reinterpret_cast<const bf16 *>(smem + stage * kStage);
     const bf16 *Vs = Ks + C::kRowTile;
     const uint32_t tr_base = tr_lane + (uint32_t)(stage * kStage);   // kStage % 512 == 0
@@ -360,14 +368,20 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
     if (wave == 0) lds_dma4_v(lse_s + q0 + lane_o, st + kLseOff);
     if (wave == 1) lds_dma4_v(delta_s + q0 + lane_o, st + kDeltaOff);
   };
-  __syncthreads();   // rows[] is written
-  if (n_steps > 0) issue(0, 0);
+  if (C::kStages == 2) {
+    __syncthreads();   // rows[] is written
+    if (n_steps > 0) issue(0, 0);
+  }
   for (int step = 0; step < n_steps; ++step) {
     __builtin_amdgcn_s_setprio(3);
+    if (C::kStages == 1) {
+      __syncthreads();                    // rows[] is written; everyone is done with the stage
+      issue(step, 0);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): my copies of this step have landed
     __syncthreads();                      // everyone's have; everyone is done with the other stage
-    const int stage = step & 1;
-    if (step + 1 < n_steps) issue(step + 1, stage ^ 1);
+    const int stage = C::kStages == 2 ? (step & 1) : 0;
+    if (C::kStages == 2 && step + 1 < n_steps) issue(step + 1, stage ^ 1);
     const bf16 *Qs = reinterpret_cast<const bf16 *>(smem + stage * kStage);
     const bf16 *Gs = Qs + C::kRowTile;
     const float *sLse = reinterpret_cast<const float *>(smem + stage * kStage + kLseOff);

@@ -145,7 +145,8 @@ struct FwdCfg {
 // workgroups on the CU compute meanwhile.  It serves the tile shapes other than block 128 / d 128 and tensors that the
 // ping-pong kernel below does not take (slabs of 4 GiB and more).
 template <int BLK, int D>
-__global__ __launch_bounds__(BLK * 2, 2) void fwd_kernel(FwdArgs a) {
+// (block 64 / d 64 fits 128 registers: four wavefronts per SIMD, 2 % faster than three)
+__global__ __launch_bounds__(BLK * 2, (BLK == 64 && D == 64) ? 4 : 2) void fwd_kernel(FwdArgs a) {
   using C = FwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
   bf16 *lds = reinterpret_cast<bf16 *>(smem);
