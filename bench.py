@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the forward kernel at the default workload (wan, density 0.25, seed 42,
 # with the O residual written): rocprofv3 FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors read
 # off the transposition kernel of the same run (profiles/wan_b128_d128_density25_step_hbm_traffic.md)
-FWD_TRAFFIC_BYTES_WAN25 = 1203128 * 1024 * 2.00 + 241116 * 1024 * 1.00
+FWD_TRAFFIC_BYTES_WAN25 = 1214770 * 1024 * 2.00 + 241118 * 1024 * 1.00
 
 
 def parse():
