@@ -113,3 +113,42 @@ def test_bwd_custom_scale_and_determinism():
     b = _run(p, qb, kb, vb, gb, mask)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("L,d,block", [(700, 128, 128), (333, 64, 64), (450, 128, 64)])
+def test_bwd_packed_qkv_layout_with_different_strides_per_tensor(L, d, block):
+    """Q, K, V live interleaved in one [B, L, 3, H, d] buffer (so do dQ, dK, dV), O and dO in a
+    [B, L, H, d] buffer: the row pitch of Q / K / V (3 H d) differs from that of O / dO (H d),
+    the tail block is ragged, and every gradient is written through its own strides."""
+    print(f"case packed L={L} d={d} block={block}", flush=True)
+    B, H = 1, 2
+    shape = (B, H, L, d)
+    qb, kb, vb, gb = (synth.make_iid(shape, L + d, 40 + s) for s in range(4))
+    st_qkv = (L * 3 * H * d, d, 3 * H * d)
+    st_o = (L * H * d, d, H * d)
+    p = binding.Params(B=B, H=H, L=L, d=d, block=block, q_stride=st_qkv, k_stride=st_qkv,
+                       v_stride=st_qkv, o_stride=st_o)
+    mask = synth.random_block_mask(p.Nb, 0.5, seed=L, slabs=B * H)
+    bufs = util.lists_from_mask(p, mask)
+    qkv = torch.empty((B, L, 3, H, d), dtype=torch.bfloat16, device="cuda")
+    for i, x in enumerate((qb, kb, vb)):
+        qkv[:, :, i] = util.dev_bf16(x).permute(0, 2, 1, 3)
+    q, k, v = (qkv[:, :, i].permute(0, 2, 1, 3) for i in range(3))          # views [B, H, L, d]
+    g = util.dev_bf16(gb).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    o = torch.zeros((B, L, H, d), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    o_lo = torch.zeros((B, L, H, d), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    lse = torch.empty((B * H, L), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(binding.asa_fwd_workspace_bytes(p))
+    binding.asa_attn_fwd(p, q, k, v, bufs["row_ptr"], bufs["col_idx"], o, lse, ws, o_lo=o_lo)
+    dqkv = torch.full((B, L, 3, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dq, dk, dv = (dqkv[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    ws = binding.alloc_workspace(binding.asa_bwd_workspace_bytes(p))
+    binding.asa_attn_bwd(p, q, k, v, o, g, lse, bufs["row_ptr"], bufs["col_idx"], bufs["col_ptr"],
+                         bufs["row_idx"], dq, dk, dv, ws, o_lo=o_lo)
+    torch.cuda.synchronize()
+    got = [util.host_f32(x.contiguous()) for x in (dq, dk, dv)]
+    qf, kf, vf, gf = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb, gb))
+    for h in range(H):
+        want = oracle.attn_bwd(qf[0, h], kf[0, h], vf[0, h], gf[0, h], mask[h], block, None)
+        for name, a, w in zip(("dQ", "dK", "dV"), got, want):
+            util.assert_close_bf16(a[0, h], w, f"packed {name}[{h}]")
