@@ -118,7 +118,19 @@ struct FwdArgs {
   const bf16 *vgt;    // [slab][Nbg][d][block]: pooled values, transposed tiles
   int Lg, Nbg;        // pooled tokens per slab, key blocks they fill
   float bias_log2;    // log2(n): the additive ln(n) of the pooled scores, in the exp2 domain
+  // Choice between the two kernels per (batch, head) slab, made on the device from the slab's
+  // tile count: 0 = this launch takes every slab; +1 = only slabs whose rows hold at least
+  // `select_min_tiles` tiles on average; -1 = only the others.
+  int select, select_min_tiles;
 };
+
+// does this launch leave the slab to the other kernel?  (wave-uniform; before any barrier)
+__device__ __forceinline__ bool slab_not_mine(const FwdArgs &a, int slab) {
+  if (a.select == 0) return false;
+  const int tiles = a.row_ptr[slab * (a.Nb + 1) + a.Nb];
+  const bool long_rows = tiles >= a.select_min_tiles * a.Nb;
+  return (a.select > 0) != long_rows;
+}
 
 template <int BLK, int D>
 struct FwdCfg {
@@ -155,6 +167,7 @@ __global__ __launch_bounds__(BLK * 2, (BLK == 64 && D == 64) ? 4 : 2) void fwd_k
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
   const int slab = work / a.Nb;
+  if (slab_not_mine(a, slab)) return;
   const int qb = work - slab * a.Nb;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -378,6 +391,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
   if (work < 0) return;
   const int slab = work / a.Nb;
+  if (slab_not_mine(a, slab)) return;
   const int qb = work - slab * a.Nb;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -858,19 +872,33 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
   if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb || a.tk.sL != D)) return hipErrorNotSupported;
   const bool prefer_pp = (BLK == 128 && D == 128 && !getenv("ASA_FWD_PLAIN")) || getenv("ASA_FWD_PINGPONG");
-  if (fits32 && (a.Nbg > 0 || prefer_pp)) {
+  FwdArgs b = a;
+  b.select = 0;
+  hipError_t e = hipSuccess;
+  // no lists (dense): every row holds Nb tiles, the same choice is made here
+  const bool dense_short = !a.row_ptr && a.Nbg == 0 && a.select_min_tiles > 0 &&
+                           a.Nb < a.select_min_tiles && !getenv("ASA_FWD_PINGPONG");
+  if (fits32 && (a.Nbg > 0 || prefer_pp) && !dense_short) {
     using P = PpCfg<BLK, D>;
+    // Short lists: the ping-pong kernel costs ~8 us per workgroup around its steady state, the
+    // lock-step kernel ~3 us; they cross at 16-20 tiles per row.  Where the rule's lower clamp
+    // does not already promise long rows, both kernels are launched and each takes the slabs
+    // that suit it (the host cannot see the lists).  ASA_FWD_PINGPONG forces one launch.
+    const bool both = a.select_min_tiles > 0 && a.Nbg == 0 && a.row_ptr && !getenv("ASA_FWD_PINGPONG");
+    if (both) b.select = 1;
     const void *fn = a.Nbg > 0 ? reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, true>)
                                : reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, false>);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
     if (e != hipSuccess) return e;
     if (a.Nbg > 0)
-      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, true>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
+      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, true>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, b);
     else
-      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, false>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, a);
-    return hipGetLastError();
+      hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, false>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, b);
+    e = hipGetLastError();
+    if (e != hipSuccess || !both) return e;
+    b.select = -1;
   }
-  hipLaunchKernelGGL((fwd_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), lds, st, a);
+  hipLaunchKernelGGL((fwd_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), lds, st, b);
   return hipGetLastError();
 }
 
@@ -888,6 +916,10 @@ hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const voi
   a.tq = pb.q; a.tk = pb.k; a.to = pb.o;
   a.H = pb.H; a.L = pb.L; a.Lpad = pb.Lpad; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs;
   a.scale_log2e = pb.scale * 1.44269504088896340736f;
+  // rows hold at least m_min tiles when the lists come from the rule: no choice to make then
+  constexpr int kPingPongMinTiles = 18;
+  a.select = 0;
+  a.select_min_tiles = pb.m_min >= kPingPongMinTiles ? 0 : kPingPongMinTiles;
   if (pb.block == 128 && pb.d == 128) return launch_fwd_t<128, 128>(a, st);
   if (pb.block == 128 && pb.d == 64) return launch_fwd_t<128, 64>(a, st);
   if (pb.block == 64 && pb.d == 128) return launch_fwd_t<64, 128>(a, st);

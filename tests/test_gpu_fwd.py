@@ -11,6 +11,18 @@ from tests import util
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["auto", "pingpong"])
+def kernel_choice(request, monkeypatch):
+    """Every test of this module runs twice: with the library's own choice of forward kernel (short
+    lists go to the lock-step kernel) and with the ping-pong kernel forced, so that both kernels
+    see every edge case."""
+    if request.param == "pingpong":
+        monkeypatch.setenv("ASA_FWD_PINGPONG", "1")
+    else:
+        monkeypatch.delenv("ASA_FWD_PINGPONG", raising=False)
+    return request.param
+
+
 def _case(B, H, L, d, block, seed):
     shape = (B, H, L, d)
     q, k, v = (synth.make_iid(shape, seed, s) for s in range(3))
@@ -86,6 +98,7 @@ def test_fwd_dense_specialisation_needs_no_lists(L, d, block):
 
 def test_fwd_single_stage_kernel_is_still_correct(monkeypatch):
     """The kernel that takes over for slabs of 4 GiB and more, forced by its switch."""
+    monkeypatch.delenv("ASA_FWD_PINGPONG", raising=False)
     monkeypatch.setenv("ASA_FWD_PLAIN", "1")
     p = binding.Params(B=1, H=2, L=1000, d=128, block=128)
     qb, kb, vb = _case(1, 2, 1000, 128, 128, seed=5)
@@ -102,6 +115,24 @@ def test_fwd_ping_pong_kernel_at_the_sizes_where_it_is_not_the_default(monkeypat
     p = binding.Params(B=1, H=2, L=L, d=d, block=block)
     qb, kb, vb = _case(1, 2, L, d, block, seed=L)
     _check_fwd(p, qb, kb, vb, synth.random_block_mask(p.Nb, 0.5, seed=L, slabs=2))
+
+
+def test_fwd_each_slab_goes_to_the_kernel_that_suits_its_lists(kernel_choice):
+    """Block 128 / d 128 without a lower retention clamp: both kernels are launched and each takes
+    the (batch, head) slabs whose rows are long / short for it.  Head 0 keeps 32 of 40 blocks per
+    row (ping-pong kernel), head 1 keeps 6 (lock-step kernel), head 2 sits just below the
+    switch-over (17 per row), head 3 just above (18); every row must come from exactly one."""
+    if kernel_choice != "auto":
+        pytest.skip("the choice is what is tested")
+    L, H = 128 * 40 - 9, 4
+    p = binding.Params(B=1, H=H, L=L, d=128, block=128)
+    qb, kb, vb = _case(1, H, L, 128, 128, seed=77)
+    mask = np.zeros((H, p.Nb, p.Nb), np.uint8)
+    rng = np.random.default_rng(7)
+    for h, m in enumerate((32, 6, 17, 18)):
+        for i in range(p.Nb):
+            mask[h, i, rng.choice(p.Nb, size=m, replace=False)] = 1
+    _check_fwd(p, qb, kb, vb, mask)
 
 
 def test_fwd_tiny_workload_with_oracle_mask():
