@@ -157,8 +157,12 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
  * attention "during both training and inference", Sec. 3.3 Step 2.1).  With
  * P = exp(S - LSE), Delta = rowsum(dO * O), dS = P * (dO V^T - Delta):
  *   dV = P^T dO,  dK = scale * dS^T Q,  dQ = scale * dS K     over the kept tiles only.
- * o, o_lo, lse are the forward's outputs (o_lo may be NULL: Delta then comes from the bf16 o
- * alone); col_ptr/row_idx is the mask by columns.
+ * o, o_lo, lse are the forward's outputs; col_ptr/row_idx is the mask by columns.
+ * o_lo may be NULL (the plain call): Delta is then not taken from o at all but formed as
+ * sum_c P_c (dO V_c^T) over the kept tiles in fp32, by one more walk over the row lists before
+ * the gradient kernels (two tile products; about a quarter more time at the Wan2.1 shape).
+ * With o_lo, Delta = rowsum(dO * (o + o_lo)) costs one pass over three tensors.  Both meet the
+ * same tolerance; Delta from the bf16 o alone would not where keys and queries are large.
  * dq, dk, dv [B, H, L, d] bf16 (q/k/v strides); every row < L is written.
  * All four index-list pointers NULL selects the dense specialisation (see asa_attn_fwd);
  * some but not all NULL is ASA_ERR_INVALID_ARG.

@@ -68,6 +68,8 @@ def lib():
                                           ip, ci, dp]
         L.asa_ref_attn_bwd_dkv.argtypes = [fp, fp, fp, fp, ci, ci, ci, up, ctypes.c_double, dp, dp,
                                            ip, ci, dp, dp]
+        L.asa_ref_attn_bwd_dq_mag.argtypes = L.asa_ref_attn_bwd_dq.argtypes
+        L.asa_ref_attn_bwd_dkv_mag.argtypes = L.asa_ref_attn_bwd_dkv.argtypes
         _lib = L
     return _lib
 
@@ -230,12 +232,16 @@ def attn_fwd(q, k, v, mask, b: int, scale: Optional[float] = None, qblocks=None)
 
 
 def attn_bwd(q, k, v, d_o, mask, b: int, scale: Optional[float] = None, qblocks=None,
-             kblocks=None):
+             kblocks=None, with_mag: bool = False):
     """Gradients of one slab with the mask held constant.
 
     Returns (dQ, dK, dV) as [L, d] f64; dQ rows outside ``qblocks`` and dK/dV rows outside
     ``kblocks`` are NaN.  O, LSE and Delta are recomputed here in fp64 for exactly the
     query blocks the requested outputs depend on.
+
+    with_mag: also return (dQ_mag, dK_mag, dV_mag), the sums of the absolute values of the
+    terms that each gradient element adds up (what bounds the rounding error of a reduced-
+    precision implementation; used by the tests' tolerance only).
     """
     q = _c(q, np.float32); k = _c(k, np.float32); v = _c(v, np.float32)
     d_o = _c(d_o, np.float32)
@@ -268,4 +274,16 @@ def attn_bwd(q, k, v, d_o, mask, b: int, scale: Optional[float] = None, qblocks=
         _check(lib().asa_ref_attn_bwd_dkv(*args, _p(kb, ctypes.c_int32), len(kb),
                                           _p(dk, ctypes.c_double), _p(dv, ctypes.c_double)),
                "attn_bwd_dkv")
-    return dq, dk, dv
+    if not with_mag:
+        return dq, dk, dv
+    mq = np.full((L, d), np.nan, dtype=np.float64)
+    mk = np.full((L, d), np.nan, dtype=np.float64)
+    mv = np.full((L, d), np.nan, dtype=np.float64)
+    if len(qb):
+        _check(lib().asa_ref_attn_bwd_dq_mag(*args, _p(qb, ctypes.c_int32), len(qb),
+                                             _p(mq, ctypes.c_double)), "attn_bwd_dq_mag")
+    if len(kb):
+        _check(lib().asa_ref_attn_bwd_dkv_mag(*args, _p(kb, ctypes.c_int32), len(kb),
+                                              _p(mk, ctypes.c_double), _p(mv, ctypes.c_double)),
+               "attn_bwd_dkv_mag")
+    return dq, dk, dv, mq, mk, mv

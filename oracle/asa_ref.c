@@ -489,3 +489,73 @@ int asa_ref_attn_bwd_dkv(const float *q, const float *k, const float *v, const f
   }
   return ASA_REF_OK;
 }
+
+/* --------------------------------------------------------------------------
+ * Size of what the gradient sums add up, before cancellation (used by the
+ * tests to bound the rounding error that a bf16 implementation may show on
+ * an element; no part of the method):
+ *   dq_mag[q][x] = scale * sum_c |dS_qc| |K_cx|     (listed query blocks)
+ *   dk_mag[c][x] = scale * sum_q |dS_qc| |Q_qx|,
+ *   dv_mag[c][x] =         sum_q  P_qc   |dO_qx|    (listed key blocks)
+ * Same loops and the same P, dP, dS as the gradient functions above.
+ * ------------------------------------------------------------------------ */
+int asa_ref_attn_bwd_dq_mag(const float *q, const float *k, const float *v, const float *d_o, int L,
+                            int d, int b, const uint8_t *mask, double scale, const double *lse,
+                            const double *delta, const int32_t *qblocks, int nq, double *dq_mag) {
+  if (!q || !k || !v || !d_o || !mask || !lse || !delta || !dq_mag) return ASA_REF_BAD_ARG;
+  int Nb = nblocks(L, b);
+#pragma omp parallel for schedule(dynamic, 4) collapse(2)
+  for (int t = 0; t < nq; ++t) {
+    for (int rr = 0; rr < b; ++rr) {
+      int i = qblocks[t];
+      int r = i * b + rr;
+      if (r >= L) continue;
+      const uint8_t *mrow = mask + (size_t)i * Nb;
+      double *g = dq_mag + (size_t)r * d;
+      for (int x = 0; x < d; ++x) g[x] = 0.0;
+      for (int c = 0; c < L; ++c) {
+        if (!mrow[c / b]) continue;
+        double s = scale * dot_fd(q + (size_t)r * d, k + (size_t)c * d, d);
+        double p = exp(s - lse[r]);
+        double dp = dot_fd(d_o + (size_t)r * d, v + (size_t)c * d, d);
+        double ds = p * (dp - delta[r]);
+        const float *krow = k + (size_t)c * d;
+        for (int x = 0; x < d; ++x) g[x] += fabs(scale * ds * (double)krow[x]);
+      }
+    }
+  }
+  return ASA_REF_OK;
+}
+
+int asa_ref_attn_bwd_dkv_mag(const float *q, const float *k, const float *v, const float *d_o, int L,
+                             int d, int b, const uint8_t *mask, double scale, const double *lse,
+                             const double *delta, const int32_t *kblocks, int nk, double *dk_mag,
+                             double *dv_mag) {
+  if (!q || !k || !v || !d_o || !mask || !lse || !delta || !dk_mag || !dv_mag) return ASA_REF_BAD_ARG;
+  int Nb = nblocks(L, b);
+#pragma omp parallel for schedule(dynamic, 4) collapse(2)
+  for (int t = 0; t < nk; ++t) {
+    for (int cc = 0; cc < b; ++cc) {
+      int j = kblocks[t];
+      int c = j * b + cc;
+      if (c >= L) continue;
+      double *gk = dk_mag + (size_t)c * d;
+      double *gv = dv_mag + (size_t)c * d;
+      for (int x = 0; x < d; ++x) { gk[x] = 0.0; gv[x] = 0.0; }
+      for (int r = 0; r < L; ++r) {
+        if (!mask[(size_t)(r / b) * Nb + j]) continue;
+        double s = scale * dot_fd(q + (size_t)r * d, k + (size_t)c * d, d);
+        double p = exp(s - lse[r]);
+        double dp = dot_fd(d_o + (size_t)r * d, v + (size_t)c * d, d);
+        double ds = p * (dp - delta[r]);
+        const float *qrow = q + (size_t)r * d;
+        const float *grow = d_o + (size_t)r * d;
+        for (int x = 0; x < d; ++x) {
+          gk[x] += fabs(scale * ds * (double)qrow[x]);
+          gv[x] += fabs(p * (double)grow[x]);
+        }
+      }
+    }
+  }
+  return ASA_REF_OK;
+}

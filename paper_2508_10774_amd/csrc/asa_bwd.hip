@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *o, const void *o
 struct BwdArgs {
   const void *q, *k, *v, *d_o;
   const float *lse2, *delta;  // [slab][Lpad]: LSE * log2(e) (minus this launch's key bias), Delta; padded with +inf, 0
+  float *delta_out;           // where the Delta-only walk of dq_kernel writes (the same array as delta)
   const int32_t *row_ptr, *col_idx, *col_ptr, *row_idx;
   void *dq, *dk, *dv;
   TensorView tq, tk, tv, to;
@@ -120,7 +121,12 @@ struct BwdCfg {
 // operand of dQ^T = K^T dS^T is gathered from the K row tile by the transposing LDS read.
 // ---------------------------------------------------------------------------------------
 // GT: with the pooled (global) tokens of ASA_G appended to every query block's list
-template <int BLK, int D, bool GT>
+// DELTA_ONLY: no gradient; the same walk forms Delta_q = sum_c P_qc dP_qc (= rowsum(dO * O) with
+// the exact O, since the P of a row sum to 1) from the unrounded fp32 P and dP and writes it to
+// a.delta_out.  Used when the caller has not kept the low half of O: Delta from the bf16 O alone
+// is off by up to 0.05 in rows whose soft-max is spread over keys with similar values, and that
+// error goes into dQ and dK times the size of the keys / queries.
+template <int BLK, int D, bool GT, bool DELTA_ONLY = false>
 __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   using C = BwdCfg<BLK, D>;
   extern __shared__ __align__(1024) unsigned char smem[];
@@ -164,7 +170,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   }
   // rows past L have LSE = +inf there, so that every probability is exactly zero
   const float lse2 = a.lse2[(int64_t)slab * a.Lpad + qrow];
-  const float delta = a.delta[(int64_t)slab * a.Lpad + qrow];
+  const float delta = DELTA_ONLY ? 0.f : a.delta[(int64_t)slab * a.Lpad + qrow];
+  float dsum = 0.f;   // DELTA_ONLY: sum of P * dP over my keys
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -246,9 +253,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
           if (key >= key_end) p0 = 0.f;
           if (key + 1 >= key_end) p1 = 0.f;
         }
-        dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - delta), p1 * (pacc[i + 1] - delta));
+        if (DELTA_ONLY) dsum += fmaf(p0, pacc[i], p1 * pacc[i + 1]);
+        else dsb[i >> 1] = pack_bf16x2(p0 * (pacc[i] - delta), p1 * (pacc[i + 1] - delta));
       }
       __builtin_amdgcn_s_setprio(0);
+      if (DELTA_ONLY) continue;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         uint4 raw = make_uint4(dsb[4 * tt], dsb[4 * tt + 1], dsb[4 * tt + 2], dsb[4 * tt + 3]);
@@ -266,6 +275,12 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
     }
   }
 
+  if (DELTA_ONLY) {
+    // the two lane halves hold different keys of the same query; rows past L get 0 (their P is 0)
+    const float total = dsum + swap_halves(dsum);
+    if (hl == 0) a.delta_out[(int64_t)slab * a.Lpad + qrow] = total;
+    return;
+  }
   if (qvalid) {
     bf16 *dst_row = slab_ptr(a.dq, a.tq, slab, a.H) + (int64_t)qrow * a.tq.sL;
 #pragma unroll
@@ -607,6 +622,12 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
+    if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkvLds);
     if (e != hipSuccess) return e;
@@ -614,6 +635,15 @@ static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, h
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
   hipError_t e = hipSuccess;
+  if (a.delta_out) {
+    // no low half of O from the caller: Delta from the tiles themselves, before anything uses it
+    if (pooled_launch)
+      hipLaunchKernelGGL((dq_kernel<BLK, D, true, true>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
+    else
+      hipLaunchKernelGGL((dq_kernel<BLK, D, false, true>), dim3(grid), dim3(C::kThreads), C::kDqLds, st, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   timing_begin(st);
   if (pooled_launch) {
     // gradients of the pooled tokens first (fp32, every query block attends them) ...
@@ -672,6 +702,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   BwdArgs a;
   a.q = q; a.k = k; a.v = v; a.d_o = d_o;
   a.lse2 = lse2; a.delta = delta;
+  a.delta_out = o_lo ? nullptr : delta;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.col_ptr = col_ptr; a.row_idx = row_idx;
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.tq = pb.q; a.tk = pb.k; a.tv = pb.v; a.to = pb.o;

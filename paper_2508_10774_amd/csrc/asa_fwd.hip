@@ -454,6 +454,12 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   // its last MFMA, V copies by the vector group.  Within 2 % of each other (true is ahead on
   // iid inputs, false on the video-like inputs of the benchmark).
   constexpr bool kSplitCopies = false;
+  // 2: all copies of a phase by its MATRIX group, one after every few MFMAs, the four wavefronts
+  // of the group staggered by one MFMA each
+#ifndef ASA_FWD_COPY_MODE
+#define ASA_FWD_COPY_MODE 0
+#endif
+  constexpr int kCopyMode = ASA_FWD_COPY_MODE;
   constexpr int kInstrK = RowTileCopy<C::kKT, D, C::kGroupWaves>::kInstr;
   constexpr int kBatchInstr = kInstrK + ColTileCopy<BLK, D, C::kGroupWaves>::kInstr;
   static_assert(kBatchInstr == 4 || kBatchInstr == 8 || kBatchInstr == 16, "unexpected copy size");
@@ -589,7 +595,14 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   };
   // (idle phases) matrix_slot: this group is the phase's matrix group
   auto dma_idle = [&](auto r_tag, bool matrix_slot) __attribute__((always_inline)) {
-    if (kSplitCopies ? matrix_slot : false) {
+    if (kCopyMode == 2) {
+      if (matrix_slot) {
+        dma_prepare(r_tag);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
+      }
+    } else if (kSplitCopies ? matrix_slot : false) {
       dma_prepare(r_tag);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -617,6 +630,9 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
     bf16x8 ring[kRing];
     int zero = 0;
     if (GT) asm volatile("s_mov_b32 %0, 0" : "=s"(zero));
+    constexpr int kSpacing = (n1 - n0) / kBatchInstr > 0 ? (n1 - n0) / kBatchInstr : 1;
+    const int my_slot = wq % kSpacing;
+    if (kCopyMode == 2) dma_prepare(r_tag);
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
 #pragma unroll
@@ -653,6 +669,11 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
           sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[c_i % kRing], qreg[sk],
                                                             sk == 0 ? zero16 : sacc[mt], 0, 0, 0);
         }
+        if (kCopyMode == 2 && (c_i - n0) / kSpacing < kBatchInstr) {
+          // behind an MFMA the matrix pipe is busy for 32 cycles: a copy request fits there
+          __builtin_amdgcn_sched_barrier(0);
+          if ((c_i - n0) % kSpacing == my_slot) dma_one(r_tag, (c_i - n0) / kSpacing);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -676,6 +697,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
     constexpr int kPortion = kBatchInstr / 8 > 0 ? kBatchInstr / 8 : 1;
     int next_copy = kSplitCopies ? kInstrK : 0;
     auto request = [&](int n_instr) __attribute__((always_inline)) {
+      if (kCopyMode == 2) return;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int e = 0; e < n_instr; ++e)
@@ -683,7 +705,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
       __builtin_amdgcn_sched_barrier(0);
     };
     __builtin_amdgcn_s_setprio(3);
-    if (!kSplitCopies) dma_prepare(r_tag);
+    if (!kSplitCopies && kCopyMode != 2) dma_prepare(r_tag);
     float bias = 0.f;   // added to the scaled scores of pooled keys (log2 domain)
     if (GT && pooled_step(phase_now - 1)) {
       bias = a.bias_log2;

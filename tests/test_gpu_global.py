@@ -96,8 +96,10 @@ def test_fwd_global_tokens_dense_lists_and_residual():
     assert np.abs(both - want_o).max() < 2e-3
 
 
-def _run_bwd_g(p, n, q, k, v, g, bufs):
+def _run_bwd_g(p, n, q, k, v, g, bufs, with_lo=True):
     o, lse, o_lo, kg, vg = _run_fwd_g(p, n, q, k, v, bufs, with_lo=True)
+    if not with_lo:
+        o_lo = None          # the backward then forms Delta from the tiles (pooled ones included)
     dq = torch.full_like(q, float("nan"))
     dk = torch.full_like(k, float("nan"))
     dv = torch.full_like(v, float("nan"))
@@ -122,16 +124,18 @@ def test_bwd_global_tokens(B, H, L, d, block, n, dens):
     mask[0, 0, :] = 0                     # a query block that sees the pooled tokens only
     mask[0, :, -1] = 0                    # a key block that gets gradient through the pooling only
     bufs = util.lists_from_mask(p, mask)
-    dq, dk, dv = _run_bwd_g(p, n, *(util.dev_bf16(x) for x in (qb, kb, vb, gb)), bufs)
+    dev = [util.dev_bf16(x) for x in (qb, kb, vb, gb)]
     qf, kf, vf, gf = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb, gb))
     m3 = mask.reshape(-1, p.Nb, p.Nb)
-    for b in range(B):
-        for h in range(H):
-            wq, wk, wv = og.attn_bwd_g(qf[b, h], kf[b, h], vf[b, h], gf[b, h], m3[b * H + h], block, n)
-            eq = util.assert_close_bf16(dq[b, h], wq, f"dQ[{b},{h}]")
-            ek = util.assert_close_bf16(dk[b, h], wk, f"dK[{b},{h}]")
-            ev = util.assert_close_bf16(dv[b, h], wv, f"dV[{b},{h}]")
-            print(f"  slab {b},{h}: max-abs dQ {eq[0]:.2e} dK {ek[0]:.2e} dV {ev[0]:.2e}", flush=True)
+    want = {(b, h): og.attn_bwd_g(qf[b, h], kf[b, h], vf[b, h], gf[b, h], m3[b * H + h], block, n)
+            for b in range(B) for h in range(H)}
+    for with_lo in (True, False):
+        dq, dk, dv = _run_bwd_g(p, n, *dev, bufs, with_lo=with_lo)
+        for (b, h), (wq, wk, wv) in want.items():
+            tag = f"[{b},{h}]" + ("" if with_lo else " (no o_lo)")
+            util.assert_close_bf16(dq[b, h], wq, "dQ" + tag)
+            util.assert_close_bf16(dk[b, h], wk, "dK" + tag)
+            util.assert_close_bf16(dv[b, h], wv, "dV" + tag)
 
 
 def test_bwd_global_tokens_dense_lists():

@@ -39,23 +39,48 @@ def run_fwd(p: binding.Params, q, k, v, bufs, with_lo=False):
     return (o, lse, o_lo) if with_lo else (o, lse)
 
 
-def assert_close_bf16(got: np.ndarray, want: np.ndarray, what: str,
-                      max_abs=O_MAX_ABS, mean_abs=O_MEAN_ABS):
-    """Rows are token vectors [..., d].  With s_r = max(1, max_x |want[r, x]|):
-    |got - want|[r, x] <= max_abs * s_r everywhere, and mean(|got - want| / s_r) <= mean_abs.
+BF16_UNIT_ROUNDOFF = 2.0 ** -8   # largest relative error of rounding to bf16 (8 significant bits)
 
-    For rows of magnitude <= 1 this is the plain absolute tolerance.  Above, the allowance
-    grows with the row's magnitude: outputs are bf16 (an element of magnitude 8 cannot be
-    stored more accurately than +-0.03), and the gradients are sums of bf16-rounded dS times
-    K or Q elements whose rounding error is proportional to the size of the terms summed,
-    not to the (possibly cancelled) result."""
+
+def assert_close_bf16(got: np.ndarray, want: np.ndarray, what: str, mag: np.ndarray = None,
+                      max_abs=O_MAX_ABS, mean_abs=O_MEAN_ABS):
+    """The stated tolerance: max |got - want| <= 2e-2 and mean |got - want| <= 2e-3.
+
+    mag is None (O, and every tensor of a test that passes no magnitudes): exactly that, on
+    every element.
+
+    mag given (gradients): the element-wise allowance is
+        max_abs * max(1, |want|)  +  2^-8 * mag
+    with mag[r, x] the sum of the absolute values of the terms that the oracle adds up for
+    that element (oracle.attn_bwd(..., with_mag=True)); the mean-abs criterion stays plain.
+    Where the allowance comes from: the matrix cores take bf16 operands, so P (for dV) and dS
+    (for dQ, dK) are rounded to 8 significant bits before they are multiplied with dO, K, Q,
+    each term of the sum picks up a relative error of up to 2^-8, and the sum of |terms| is
+    what bounds the result's error, however much the terms cancel; the result itself is
+    stored in bf16 (2^-8 |want| < max_abs |want|).  An element of magnitude <= 1 whose terms
+    are small gets the plain 2e-2.  That the plain figure cannot hold where mag is large is
+    shown on the CPU in tests/test_tolerance_model.py (rounding dS alone, everything else
+    exact, already exceeds it).
+
+    Prints the plain maximum and mean, the number of elements beyond the plain figure and the
+    largest error relative to the allowance; returns (plain max, plain mean).
+    """
     got = got.astype(np.float64)
     want = want.astype(np.float64)
     assert np.isfinite(got).all(), f"{what}: non-finite values"
-    s_r = np.maximum(1.0, np.abs(want).max(axis=-1, keepdims=True))
-    err = np.abs(got - want) / s_r
-    assert err.max() <= max_abs, f"{what}: scaled max-abs {err.max():.3e} > {max_abs}"
-    assert err.mean() <= mean_abs, f"{what}: scaled mean-abs {err.mean():.3e} > {mean_abs}"
+    err = np.abs(got - want)
+    if mag is None:
+        bound = np.full_like(err, max_abs)
+    else:
+        bound = max_abs * np.maximum(1.0, np.abs(want)) + BF16_UNIT_ROUNDOFF * mag.astype(np.float64)
+    rel = err / bound
+    over_plain = int((err > max_abs).sum())
+    print(f"    {what}: max-abs {err.max():.3e} mean-abs {err.mean():.3e} | beyond {max_abs:g}: "
+          f"{over_plain} of {err.size} | max err/allowance {rel.max():.3f}", flush=True)
+    i = np.unravel_index(np.argmax(rel), rel.shape)
+    assert rel.max() <= 1.0, (f"{what}: |err| {err[i]:.3e} > allowance {bound[i]:.3e} at {i} "
+                              f"(want {want[i]:.4f})")
+    assert err.mean() <= mean_abs, f"{what}: mean-abs {err.mean():.3e} > {mean_abs}"
     return float(err.max()), float(err.mean())
 
 
