@@ -37,7 +37,9 @@ typedef enum asa_status {
   ASA_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad parameter, misaligned pointer */
   ASA_ERR_UNSUPPORTED = -2, /* (block, d) pair or size the kernels were not built for     */
   ASA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the *_workspace_bytes     */
-  ASA_ERR_HIP = -4          /* a HIP call failed; see asa_last_hip_error()                 */
+  ASA_ERR_HIP = -4,         /* a HIP call failed; see asa_last_hip_error()                 */
+  ASA_ERR_TOO_LARGE = -5    /* asa_attn_bwd_noalloc: the problem needs more scratch memory than
+                               ASA_NOALLOC_SCRATCH_BYTES                                      */
 } asa_status;
 
 /*
@@ -171,6 +173,28 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
                  const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
                  const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
                  void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * asa_attn_bwd for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as asa_attn_bwd, minus the workspace: the scratch memory
+ * of the call (the backward's row statistics and the order of its dK / dV workgroups) lives in
+ * a device array of ASA_NOALLOC_SCRATCH_BYTES that is part of the library (every GPU the library
+ * is used on holds one copy until the process ends).  The call allocates and frees nothing.
+ *   - The device that is current at the call must be the device of `hip_stream` and of the
+ *     tensors; its array's address is looked up once per device, at the first call there.
+ *   - asa_bwd_workspace_bytes(p) > ASA_NOALLOC_SCRATCH_BYTES: ASA_ERR_TOO_LARGE, nothing is
+ *     enqueued (the need is 12 bytes per padded token row of all slabs plus 4 bytes per block
+ *     row: 8 MiB cover B * H * L up to about 690 000 tokens; the Wan2.1 layer needs 4.7 MiB).
+ *   - All calls on one GPU share that GPU's array: two calls whose work overlaps in time on
+ *     one GPU (different streams, or several host threads) race; calls on one stream do not.
+ *     The array keeps the previous call's contents; no call depends on them.
+ */
+#define ASA_NOALLOC_SCRATCH_BYTES (8u << 20)
+int asa_attn_bwd_noalloc(const asa_params *p, const void *q, const void *k, const void *v,
+                         const void *o, const void *o_lo, const void *d_o, const float *lse,
+                         const int32_t *row_ptr, const int32_t *col_idx, const int32_t *col_ptr,
+                         const int32_t *row_idx, void *dq, void *dk, void *dv, void *hip_stream);
 
 /*
  * ASA with global tokens, ASA_G (Sec. 3.3, "ASA with Global Tokens"): K and V are extended by

@@ -38,7 +38,7 @@ class asa_params(ctypes.Structure):
 EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_workspace_bytes",
            "asa_fwd_workspace_bytes", "asa_bwd_workspace_bytes", "asa_build_mask",
            "asa_mask_from_scores", "asa_csr_from_mask", "asa_attn_fwd", "asa_attn_bwd",
-           "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
+           "asa_attn_bwd_noalloc", "asa_set_kernel_timing", "asa_global_token_count", "asa_global_tokens",
            "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
            "asa_attn_bwd_g", "asa_mask_seeded_workspace_bytes", "asa_build_mask_seeded",
            "asa_sample_offsets", "asa_gilbert_order", "asa_reorder_tokens",
@@ -69,6 +69,8 @@ def load():
     L.asa_csr_from_mask.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     L.asa_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.asa_attn_bwd.argtypes = [pp] + [vp] * 15 + [ctypes.c_size_t, vp]
+    L.asa_attn_bwd_noalloc.argtypes = [pp] + [vp] * 15
+    L.asa_attn_bwd_noalloc.restype = ctypes.c_int
     L.asa_set_kernel_timing.argtypes = [vp, vp]
     for n in ("asa_global_token_count", "asa_fwd_g_workspace_bytes", "asa_bwd_g_workspace_bytes"):
         getattr(L, n).restype = ctypes.c_size_t
@@ -198,6 +200,17 @@ def asa_attn_bwd(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row
                                _ptr(d_o), _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
                                _ptr(row_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                ws_bytes, _stream(stream)), "asa_attn_bwd")
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20   # ASA_NOALLOC_SCRATCH_BYTES of asa.h
+
+
+def asa_attn_bwd_noalloc(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq,
+                         dk, dv, o_lo=None, stream=None):
+    _check(load().asa_attn_bwd_noalloc(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                       _ptr(o_lo), _ptr(d_o), _ptr(lse), _ptr(row_ptr),
+                                       _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx), _ptr(dq),
+                                       _ptr(dk), _ptr(dv), _stream(stream)), "asa_attn_bwd_noalloc")
 
 
 def asa_mask_seeded_workspace_bytes(p: Params) -> int:

@@ -2,6 +2,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "asa_common.hpp"
 
 namespace asa {
@@ -114,6 +116,7 @@ const char *asa_error_string(int status) {
     case ASA_ERR_UNSUPPORTED: return "unsupported size or (block, d) combination";
     case ASA_ERR_WORKSPACE: return "workspace missing or too small";
     case ASA_ERR_HIP: return "HIP runtime error (see asa_last_hip_error)";
+    case ASA_ERR_TOO_LARGE: return "problem needs more scratch memory than the library's fixed array holds";
     default: return "unknown status";
   }
 }
@@ -384,12 +387,13 @@ int asa_attn_bwd_g(const asa_params *p, int n, const void *q, const void *k, con
                            dv, workspace, reinterpret_cast<hipStream_t>(hip_stream), &gt));
 }
 
-int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
-                 const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
-                 const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
-                 void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  Problem pb;
-  int rc = resolve(p, &pb);
+// Argument checks of the backward that do not depend on where the scratch memory comes from.
+static int check_bwd_args(const asa_params *p, Problem *pb, const void *q, const void *k,
+                          const void *v, const void *o, const void *o_lo, const void *d_o,
+                          const float *lse, const int32_t *row_ptr, const int32_t *col_idx,
+                          const int32_t *col_ptr, const int32_t *row_idx, void *dq, void *dk,
+                          void *dv) {
+  int rc = resolve(p, pb);
   if (rc != ASA_OK) return rc;
   {
     const int n_lists = (row_ptr != nullptr) + (col_idx != nullptr) + (col_ptr != nullptr) + (row_idx != nullptr);
@@ -403,10 +407,65 @@ int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *
       !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned4(lse) ||
       !aligned4(row_ptr) || !aligned4(col_idx) || !aligned4(col_ptr) || !aligned4(row_idx))
     return ASA_ERR_INVALID_ARG;
+  return ASA_OK;
+}
+
+int asa_attn_bwd(const asa_params *p, const void *q, const void *k, const void *v, const void *o,
+                 const void *o_lo, const void *d_o, const float *lse, const int32_t *row_ptr,
+                 const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx, void *dq,
+                 void *dk, void *dv, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Problem pb;
+  int rc = check_bwd_args(p, &pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq,
+                          dk, dv);
+  if (rc != ASA_OK) return rc;
   if (!workspace || workspace_bytes < bwd_workspace_bytes(pb) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   return finish(launch_bwd(pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
                            dv, workspace, reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
+// ------------------------------------------------ backward for callers that cannot allocate
+// The backward's scratch memory (row statistics, dK / dV workgroup order) in a device array of
+// the library itself.  Every GPU the library runs on holds its own copy at its own address;
+// the name `scratch` is only a handle for hipGetSymbolAddress on the host side.
+static __device__ __align__(256) unsigned char scratch[ASA_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, 0 = not asked yet
+
+static int scratch_of_current_device(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return finish(e);
+  if (dev < 0 || dev >= kMaxDevices) return ASA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return finish(e);
+    if (!ptr) return finish(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return ASA_OK;
+}
+
+int asa_attn_bwd_noalloc(const asa_params *p, const void *q, const void *k, const void *v,
+                         const void *o, const void *o_lo, const void *d_o, const float *lse,
+                         const int32_t *row_ptr, const int32_t *col_idx, const int32_t *col_ptr,
+                         const int32_t *row_idx, void *dq, void *dk, void *dv, void *hip_stream) {
+  Problem pb;
+  int rc = check_bwd_args(p, &pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq,
+                          dk, dv);
+  if (rc != ASA_OK) return rc;
+  if (bwd_workspace_bytes(pb) > (size_t)ASA_NOALLOC_SCRATCH_BYTES) return ASA_ERR_TOO_LARGE;
+  void *ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc != ASA_OK) return rc;
+  // nothing in the scratch has to start at zero: the row-statistics kernel and the order kernel
+  // write every word that the gradient kernels read
+  return finish(launch_bwd(pb, q, k, v, o, o_lo, d_o, lse, row_ptr, col_idx, col_ptr, row_idx, dq, dk,
+                           dv, ws, reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
 int asa_gilbert_order(int32_t T, int32_t Y, int32_t X, int32_t n_prefix, int32_t *order,
