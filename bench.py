@@ -30,10 +30,15 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the forward kernel at the default workload (wan, density 0.25, seed 42,
-# with the O residual written): rocprofv3 FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors read
-# off the transposition kernel of the same run (profiles/wan_b128_d128_density25_step_hbm_traffic.md)
-FWD_TRAFFIC_BYTES_WAN25 = 1214770 * 1024 * 2.00 + 241118 * 1024 * 1.00
+# HBM bytes per launch of every kernel of the default step (wan, density 0.25, seed 42), written by
+# `bench.py --pmc-summary` from the two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE) whose
+# commands the file itself records; bench.py only reads it
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "wan_b128_d128_density25_step_hbm_traffic.json")
+# tau of the variable-m operating point: the fp32 value 1 - 4 * 2^-24.  With the retention clamps
+# left open (r_min = 0, r_max = 1) the rule of Alg. 3 step 9 then keeps 25.7 % of the blocks of the
+# synthetic Wan tokens (seed 42), between 2 and 244 per row (the oracle gives the same figure:
+# tests/test_oracle_operating_point.py)
+VARIABLE_M_TAU = float(np.float32(1.0) - np.float32(4.0 * 2.0 ** -24))
 
 
 def parse():
@@ -52,12 +57,88 @@ def parse():
     ap.add_argument("--no-asa-g", action="store_true")
     ap.add_argument("--no-gilbert", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="the timed steps only (for rocprofv3): no side measurements, no CPU baseline")
     ap.add_argument("--cpu-sample-slabs", type=int, default=12)
+    ap.add_argument("--no-variable-m", action="store_true")
+    ap.add_argument("--no-cog", action="store_true")
+    ap.add_argument("--pmc-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU work: turn the counter CSVs of two rocprofv3 --pmc passes over this "
+                         "script (FETCH_SIZE, then WRITE_SIZE) into " + os.path.relpath(TRAFFIC_FILE, ROOT))
     return ap.parse_args()
+
+
+def pmc_summary(fetch_dir, write_dir):
+    """HBM bytes per launch of every asa:: kernel from two rocprofv3 --pmc passes (KiB per
+    dispatch, averaged), scaled by what the same counters read for the V transposition kernel,
+    a plain copy of known size.  Writes TRAFFIC_FILE."""
+    import collections
+    import csv
+    import glob
+
+    def read(d, counter):
+        files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+        assert files, f"no counter_collection.csv under {d}"
+        acc = collections.defaultdict(list)
+        for f in files:
+            for r in csv.DictReader(open(f)):
+                if r["Counter_Name"] == counter and "asa::" in r["Kernel_Name"]:
+                    name = r["Kernel_Name"].split("(")[0].replace("void ", "").strip()
+                    acc[name].append(float(r["Counter_Value"]))
+        return {k: (float(np.mean(v)), len(v)) for k, v in acc.items()}
+
+    fetch, write = read(fetch_dir, "FETCH_SIZE"), read(write_dir, "WRITE_SIZE")
+    from paper_2508_10774_amd import synth
+    w = synth.WAN
+    lpad = w.Nb * w.block
+    copy = [k for k in fetch if "transpose_kernel" in k]
+    assert copy, "the calibration kernel (transpose_kernel) is not in the trace"
+    read_kib = w.B * w.H * w.L * w.d * 2 / 1024.0          # what it reads: V once
+    write_kib = w.B * w.H * lpad * w.d * 2 / 1024.0        # what it writes: the padded tiles
+    f_fac = read_kib / fetch[copy[0]][0]
+    w_fac = write_kib / write[copy[0]][0]
+    kernels = {}
+    for k in sorted(set(fetch) | set(write)):
+        fk, wk = fetch.get(k, (0.0, 0)), write.get(k, (0.0, 0))
+        kernels[k] = {"dispatches": fk[1], "fetch_size_kib": round(fk[0], 1), "write_size_kib": round(wk[0], 1),
+                      "read_bytes": round(fk[0] * 1024 * f_fac), "written_bytes": round(wk[0] * 1024 * w_fac)}
+    out = {"workload": "wan2.1-1.3b, density 0.25 (fixed budget), seed 42, one step = mask + forward + backward",
+           "commands": ["rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o fetch -- "
+                        "python3 bench.py --steps 3 --warmup 1 --profile-run",
+                        "rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o write -- "
+                        "python3 bench.py --steps 3 --warmup 1 --profile-run",
+                        "python3 bench.py --pmc-summary gpurun_out/pmc_fetch gpurun_out/pmc_write"],
+           "calibration": {"kernel": copy[0], "known_read_kib": round(read_kib, 1), "known_write_kib": round(write_kib, 1),
+                           "fetch_factor": round(f_fac, 4), "write_factor": round(w_fac, 4)},
+           "kernels": kernels}
+    with open(TRAFFIC_FILE, "w") as fh:
+        json.dump(out, fh, indent=1)
+        fh.write("\n")
+    print(json.dumps(out["calibration"]))
+    for k, v in kernels.items():
+        print(f"{k}: read {v['read_bytes'] / 1e6:.1f} MB written {v['written_bytes'] / 1e6:.1f} MB")
+
+
+def traffic_of(kernel_prefix):
+    """HBM bytes per launch of the kernel whose name starts with kernel_prefix, from TRAFFIC_FILE."""
+    try:
+        t = json.load(open(TRAFFIC_FILE))
+        for k, v in t["kernels"].items():
+            if k.replace("asa::", "").replace(" ", "").startswith(kernel_prefix.replace(" ", "")):
+                return v["read_bytes"] + v["written_bytes"]
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def main():
     args = parse()
+    if args.pmc_summary:
+        pmc_summary(*args.pmc_summary)
+        return
+    if args.profile_run:
+        args.no_cpu_baseline = args.no_sweep = args.no_gilbert = args.no_asa_g = args.no_dense_ref = True
+        args.no_variable_m = args.no_cog = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; ASA shards over heads with no exchange, so "
               "--gpus N>1 would only repeat the single-GPU kernel on H/N heads. Use --gpus 1.",
@@ -121,6 +202,49 @@ def main():
         if events:
             events["s3"].record(stream)
 
+    def measure_point(pp, tq, tk, tv, reps=10, skip=3, with_bwd=None):
+        """mask + forward (+ backward) of one operating point, outside the timed steps: medians."""
+        b2 = binding.alloc_index_lists(pp)
+        wm = binding.alloc_workspace(binding.asa_mask_workspace_bytes(pp))
+        wf = binding.alloc_workspace(binding.asa_fwd_workspace_bytes(pp))
+        oo = torch.empty_like(tq)
+        ll = torch.empty((pp.B * pp.H, pp.L), dtype=torch.float32, device="cuda")
+        if with_bwd is not None:
+            lo = torch.empty_like(tq)
+            wb = binding.alloc_workspace(binding.asa_bwd_workspace_bytes(pp))
+            g1, g2, g3 = torch.empty_like(tq), torch.empty_like(tq), torch.empty_like(tq)
+        evs = [[ev() for _ in range(6)] for _ in range(reps)]
+        for e6 in evs:
+            e6[0].record(stream)
+            binding.asa_build_mask(pp, tq, tk, b2["mask"], b2["row_ptr"], b2["col_idx"], b2["col_ptr"],
+                                   b2["row_idx"], None, wm)
+            e6[1].record(stream)
+            binding.asa_set_kernel_timing(e6[4], e6[5])
+            binding.asa_attn_fwd(pp, tq, tk, tv, b2["row_ptr"], b2["col_idx"], oo, ll, wf,
+                                 o_lo=None if with_bwd is None else lo)
+            e6[2].record(stream)
+            if with_bwd is not None:
+                binding.asa_attn_bwd(pp, tq, tk, tv, oo, with_bwd, ll, b2["row_ptr"], b2["col_idx"],
+                                     b2["col_ptr"], b2["row_idx"], g1, g2, g3, wb, o_lo=lo)
+            e6[3].record(stream)
+        torch.cuda.synchronize()
+        med = lambda a, b: float(np.median([e6[a].elapsed_time(e6[b]) for e6 in evs[skip:]]))
+        rl = (b2["row_ptr"][:, 1:] - b2["row_ptr"][:, :-1]).cpu().numpy().reshape(-1)
+        tiles = int(rl.sum())
+        fl = tiles * 4.0 * pp.block * pp.block * pp.d
+        r = {"density": round(tiles / (pp.B * pp.H * pp.Nb * pp.Nb), 5), "executed_tiles": tiles,
+             "tiles_per_row": {"min": int(rl.min()), "median": float(np.median(rl)), "max": int(rl.max())},
+             "mask_ms": round(med(0, 1), 4), "fwd_ms": round(med(1, 2), 4),
+             "fwd_tflops": round(fl / (med(1, 2) * 1e-3) / 1e12, 1),
+             "fwd_frac_of_bf16_peak": round(fl / (med(1, 2) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+             "fwd_kernel_ms": round(med(4, 5), 4),
+             "fwd_kernel_tflops": round(fl / (med(4, 5) * 1e-3) / 1e12, 1),
+             "fwd_kernel_frac_of_bf16_peak": round(fl / (med(4, 5) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        if with_bwd is not None:
+            r["bwd_ms"] = round(med(2, 3), 4)
+            r["bwd_tflops"] = round(2.5 * fl / (med(2, 3) * 1e-3) / 1e12, 1)
+        return r, b2, oo
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -133,7 +257,23 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3
 
+    o_host = o.cpu() if not args.no_cpu_baseline else None    # the timed steps' O, for the oracle to check
+
     side_errors = {}   # a side measurement that fails must not take the headline line with it
+    # The same 25 % of the blocks chosen by the threshold itself: tau just below 1 and open
+    # retention clamps, so that every row gets its own number of key blocks (Alg. 3 step 9) and
+    # the forward meets rows of very different length (it takes them longest first).
+    variable_m = None
+    try:
+        if not args.no_variable_m and args.workload == "wan":
+            p_v = binding.Params(B=w.B, H=w.H, L=w.L, d=w.d, block=w.block, k_samples=w.k_samples,
+                                 tau=VARIABLE_M_TAU, r_min=0.0, r_max=1.0, n_prefix_dense=w.n_text)
+            variable_m, _b, _o = measure_point(p_v, q, k, v, with_bwd=None if args.no_bwd else g)
+            variable_m["setting"] = f"tau = 1 - 4 * 2^-24 = {VARIABLE_M_TAU!r}, r_min = 0, r_max = 1 (open clamps)"
+            del _b, _o
+    except Exception as exc:   # noqa: BLE001
+        side_errors['variable_m'] = repr(exc)
+        torch.cuda.synchronize()
     # the same step captured into a HIP graph and replayed (the library allocates nothing and
     # records no memset nodes): what is left of the step when the launches cost nothing
     graph_ms = None
@@ -344,6 +484,15 @@ def main():
         side_errors['gilbert'] = repr(exc)
         torch.cuda.synchronize()
 
+    # CogVideoX-5B attention shape (block 64, d 64, 226 always-kept text tokens), 20 % fixed budget
+    cog = None
+    try:
+        if not args.no_cog and args.workload == "wan":
+            cog = cog_point(args, binding, synth, torch, measure_point, dev)
+    except Exception as exc:   # noqa: BLE001
+        side_errors['cog'] = repr(exc)
+        torch.cuda.synchronize()
+
     mask_ms = np.array([e["s0"].elapsed_time(e["s1"]) for e in per_step])
     fwd_ms = np.array([e["s1"].elapsed_time(e["s2"]) for e in per_step])
     bwd_ms = np.array([e["s2"].elapsed_time(e["s3"]) for e in per_step])
@@ -400,6 +549,8 @@ def main():
         "seeded_sampling_mask_ms": None if seeded_mask_ms is None else round(seeded_mask_ms, 4),
         "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),
+        "variable_m": variable_m,
+        "cog": cog,
         "asa_g": asa_g,
         "gilbert": gil,
         "density_sweep": sweep,
@@ -417,9 +568,9 @@ def main():
             "frac_of_measured_mfma_only_rate": (None if measured is None else
                                                 round(float(kern_tflops / measured["mfma_only_tflops"]), 4)),
             "flops_per_launch": fwd_flops,
-            "traffic": (round(FWD_TRAFFIC_BYTES_WAN25) if (args.workload == "wan" and abs(dens - 0.25) < 1e-9
-                                                           and args.seed == 42 and not args.no_bwd) else None),
-            "traffic_unit": "HBM bytes per launch, from the committed rocprofv3 counter summary",
+            "traffic": (traffic_of(f"fwd_pp_kernel<{p.block},{p.d}") if (
+                args.workload == "wan" and abs(dens - 0.25) < 1e-9 and args.seed == 42) else None),
+            "traffic_unit": "HBM bytes per launch, from " + os.path.relpath(TRAFFIC_FILE, ROOT),
         },
         "paper_context": "BLADE reports 22.21 ms ASA vs 73.25 ms dense FA2 on one H20 at this shape "
                          "(sparsity 0.798) and 14.10x / 8.89x end-to-end speedups; other hardware, "
@@ -429,23 +580,66 @@ def main():
 
     if not args.no_cpu_baseline:
         try:
-            out["cpu_baseline"] = cpu_baseline(p, w, qb, kb, vb, bufs, args.cpu_sample_slabs, tile_flops)
+            out["cpu_baseline"] = cpu_baseline(p, w, qb, kb, vb, bufs, args.cpu_sample_slabs, tile_flops,
+                                               o_host)
         except Exception as exc:   # noqa: BLE001  (the GPU figures above stand on their own)
             out["cpu_baseline"] = {"value": None, "unit": "TFLOP/s", "cores": None, "kind": "oracle",
                                    "sample": "failed: " + repr(exc)}
     print(json.dumps(out))
 
 
-def cpu_baseline(p, w, qb, kb, vb, bufs, n_slabs, tile_flops):
+def cog_point(args, binding, synth, torch, measure_point, dev):
+    """CogVideoX shape: GPU mask + forward + backward, and the oracle on three heads beside it."""
+    import oracle
+    w = synth.COG
+    dens = 0.20
+    pc = binding.Params(B=w.B, H=w.H, L=w.L, d=w.d, block=w.block, k_samples=w.k_samples, tau=0.9,
+                        r_min=dens, r_max=dens, n_prefix_dense=w.n_text)
+    qb, kb, vb = synth.make_qkv(w, args.seed)
+    gb = synth.make_do(w, args.seed)
+    q, k, v, g = dev(qb), dev(kb), dev(vb), dev(gb)
+    r, bufs, o = measure_point(pc, q, k, v, with_bwd=None if args.no_bwd else g)
+    r["setting"] = (f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} block={w.block}, tau=0.9, "
+                    f"r_min=r_max={dens} (fixed budget) + {w.n_text} always-kept text tokens, seed={args.seed}")
+    r["kernel"] = f"fwd_kernel<{w.block},{w.d}>"
+    if not args.no_cpu_baseline:
+        heads = [0, w.H // 2, w.H - 1]
+        offs = synth.default_sample_offsets(w.block, w.k_samples)
+        gm = bufs["mask"].cpu().numpy()
+        oh = o.float().cpu().numpy()
+        t_mask = t_fwd = 0.0
+        same, errs = [], []
+        for h in heads:
+            qf, kf, vf = (synth.bf16_bits_to_f32(x[0, h]) for x in (qb, kb, vb))
+            t0 = time.perf_counter()
+            m, _ = oracle.build_mask(qf[None, None], kf[None, None], w.block, offs, 0.9, dens, dens, w.n_text)
+            t1 = time.perf_counter()
+            wo, _ = oracle.attn_fwd(qf, kf, vf, m[0, 0], w.block)
+            t_fwd += time.perf_counter() - t1
+            t_mask += t1 - t0
+            same.append(bool(np.array_equal(m[0, 0], gm[h])))
+            if same[-1]:
+                errs.append(np.abs(oh[0, h] - wo))
+        r["oracle"] = {"heads": heads, "mask_s": round(t_mask, 2), "fwd_s": round(t_fwd, 2),
+                       "cores": oracle.num_threads(),
+                       "gpu_mask_identical": f"{sum(same)}/{len(same)}",
+                       "o_max_abs_err": None if not errs else float(max(e.max() for e in errs)),
+                       "o_mean_abs_err": None if not errs else float(np.mean([e.mean() for e in errs]))}
+    return r
+
+
+def cpu_baseline(p, w, qb, kb, vb, bufs, n_slabs, tile_flops, o_host=None):
     """The oracle as it stands (never tuned for this), timed on the host cores on a bounded
-    sample of the same workload: its own mask path and its fp64 forward for `n_slabs` slabs."""
+    sample of the same workload: its own mask path and its fp64 forward for `n_slabs` slabs.
+    Where the GPU's mask of a slab is the oracle's, the GPU's O of that slab (from the timed
+    steps) is compared with the oracle's, every row."""
     import oracle
     from paper_2508_10774_amd import synth
     heads = sorted(set(int(x) for x in np.linspace(0, p.H - 1, min(n_slabs, p.H))))
     offs = synth.default_sample_offsets(p.block, p.k_samples)
     oracle.attn_fwd(*(synth.bf16_bits_to_f32(x[0, 0, :256]) for x in (qb, kb, vb)),
                     np.ones((256 // p.block,) * 2, np.uint8), p.block)          # load the library
-    tiles, t_mask, t_fwd, agree = 0, 0.0, 0.0, []
+    tiles, t_mask, t_fwd, agree, o_err = 0, 0.0, 0.0, [], []
     gpu_mask = bufs["mask"].cpu().numpy()
     for h in heads:
         qf, kf, vf = (synth.bf16_bits_to_f32(x[0, h]) for x in (qb, kb, vb))
@@ -453,12 +647,15 @@ def cpu_baseline(p, w, qb, kb, vb, bufs, n_slabs, tile_flops):
         m, _ = oracle.build_mask(qf[None, None], kf[None, None], p.block, offs, p.tau, p.r_min,
                                  p.r_max, p.n_prefix_dense)
         t1 = time.perf_counter()
-        oracle.attn_fwd(qf, kf, vf, m[0, 0], p.block)
+        wo, _ = oracle.attn_fwd(qf, kf, vf, m[0, 0], p.block)
         t2 = time.perf_counter()
         t_mask += t1 - t0
         t_fwd += t2 - t1
         tiles += int(m.sum())
         agree.append(bool(np.array_equal(m[0, 0], gpu_mask[h])))
+        if agree[-1] and o_host is not None:
+            err = np.abs(o_host[0, h].float().numpy().astype(np.float64) - wo)
+            o_err.append((float(err.max()), float(err.mean())))
     return {
         "value": round(tiles * tile_flops / t_fwd / 1e12, 6),
         "unit": "TFLOP/s",
@@ -467,6 +664,10 @@ def cpu_baseline(p, w, qb, kb, vb, bufs, n_slabs, tile_flops):
         "sample": f"fp64 oracle forward of heads {heads} of batch 0 ({tiles} tiles) in {t_fwd:.2f} s; "
                   f"its mask path for the same heads in {t_mask:.2f} s; "
                   f"GPU mask identical to the oracle's on {sum(agree)}/{len(agree)} of them",
+        "gpu_o_vs_oracle": None if not o_err else {
+            "slabs": len(o_err), "rows_per_slab": p.L,
+            "max_abs_err": max(e[0] for e in o_err), "mean_abs_err": float(np.mean([e[1] for e in o_err])),
+            "tolerance": "max-abs 2e-2, mean-abs 2e-3"},
     }
 
 

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasa.so")
-SOURCES = ["asa_api.hip", "asa_fwd.hip", "asa_mask.hip", "asa_bwd.hip", "asa_reorder.hip"]
+SOURCES = ["asa_api.hip", "asa_fwd.hip", "asa_mask.hip", "asa_bwd.hip", "asa_reorder.hip", "asa_order.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -138,10 +138,15 @@ size_t asa_mask_workspace_bytes(const asa_params *p) {
   return probe_workspace_bytes(pb) + round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
 }
 
+static size_t fwd_order_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.Nb * sizeof(int32_t));
+}
+
 size_t asa_fwd_workspace_bytes(const asa_params *p) {
   Problem pb;
   if (resolve(p, &pb) != ASA_OK) return 0;
-  return transposed_bytes(pb);  // V as [slab][d][Lpad]
+  // V as [slab][Nb][d][block], then the order of the workgroups
+  return transposed_bytes(pb) + fwd_order_bytes(pb);
 }
 
 size_t asa_bwd_workspace_bytes(const asa_params *p) {
@@ -249,13 +254,20 @@ int asa_attn_fwd(const asa_params *p, const void *q, const void *k, const void *
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||
       !aligned4(lse) || !aligned4(row_ptr) || !aligned4(col_idx))
     return ASA_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < transposed_bytes(pb) || !aligned16(workspace))
+  if (!workspace || workspace_bytes < transposed_bytes(pb) + fwd_order_bytes(pb) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = launch_transpose(pb, v, pb.v, workspace, st);
   if (e != hipSuccess) return finish(e);
+  // rows of uneven length (the rule's own m per row): longest first inside each XCD's share
+  int32_t *order = nullptr;
+  if (row_ptr && length_order_fits(pb.n_slabs * pb.Nb)) {
+    order = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(workspace) + transposed_bytes(pb));
+    e = launch_length_order(row_ptr, pb.Nb, pb.n_slabs * pb.Nb, order, st);
+    if (e != hipSuccess) return finish(e);
+  }
   timing_begin(st);
-  e = launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, o_lo, lse, st);
+  e = launch_fwd(pb, q, k, workspace, row_ptr, col_idx, o, o_lo, lse, order, st);
   timing_end(st);
   return finish(e);
 }
@@ -312,7 +324,7 @@ size_t asa_fwd_g_workspace_bytes(const asa_params *p, int n) {
   Problem pb;
   int Lg, Nbg;
   if (resolve(p, &pb) != ASA_OK || global_dims(pb, n, &Lg, &Nbg) != ASA_OK) return 0;
-  return transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg);
+  return transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg) + fwd_order_bytes(pb);
 }
 
 int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, const void *v,
@@ -332,7 +344,7 @@ int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, con
     return ASA_ERR_INVALID_ARG;
   if ((uint64_t)pb.Nb * pb.block * (uint64_t)pb.k.sL * 2u >= 0xFFFFFFFFull) return ASA_ERR_UNSUPPORTED;
   if (pb.k.sL != pb.d) return ASA_ERR_UNSUPPORTED;   // rows of K must be contiguous here
-  if (!workspace || workspace_bytes < transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg) ||
+  if (!workspace || workspace_bytes < transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg) + fwd_order_bytes(pb) ||
       !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
@@ -345,8 +357,14 @@ int asa_attn_fwd_g(const asa_params *p, int n, const void *q, const void *k, con
   if (e != hipSuccess) return finish(e);
   GlobalTokens gt;
   gt.n = n; gt.Lg = Lg; gt.Nbg = Nbg; gt.kg = kg; gt.vg = vg; gt.vgt = vgt;
+  int32_t *order = nullptr;
+  if (row_ptr && length_order_fits(pb.n_slabs * pb.Nb)) {
+    order = reinterpret_cast<int32_t *>(ws + transposed_bytes(pb) + pooled_tile_bytes(pb, Nbg));
+    e = launch_length_order(row_ptr, pb.Nb, pb.n_slabs * pb.Nb, order, st);
+    if (e != hipSuccess) return finish(e);
+  }
   timing_begin(st);
-  e = launch_fwd(pb, q, k, ws, row_ptr, col_idx, o, o_lo, lse, st, &gt);
+  e = launch_fwd(pb, q, k, ws, row_ptr, col_idx, o, o_lo, lse, order, st, &gt);
   timing_end(st);
   return finish(e);
 }

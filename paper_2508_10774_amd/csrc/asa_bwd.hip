@@ -536,44 +536,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void dkv_kernel(BwdArgs a) {
   emit(vacc, true);
 }
 
-// ---------------------------------------------------------------------------------------
-// Order of the dK / dV workgroups.  Columns of the mask differ a lot in length (31..220 query
-// blocks at 25 % density on video-like inputs) and a long one that starts late ends the kernel
-// late.  Each XCD keeps its contiguous share of the (slab, key block) items (they share an L2)
-// but works through it longest column first.  One workgroup per XCD share: bitonic sort of
-// (length descending, item ascending) keys in LDS.
-// ---------------------------------------------------------------------------------------
-constexpr int kOrderMax = 2048;   // items per XCD share that the sort handles
-__global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t *col_ptr, int Nb, int total,
-                                                         int32_t *order) {
-  __shared__ uint64_t key[kOrderMax];
-  const int share = (total + kNumXcd - 1) / kNumXcd;
-  const int first = blockIdx.x * share;
-  const int count = max(0, min(share, total - first));
-  for (int t = threadIdx.x; t < kOrderMax; t += 1024) {
-    uint64_t kk = ~0ull;                       // padding sorts last
-    if (t < count) {
-      const int item = first + t, slab = item / Nb, kb = item - slab * Nb;
-      const uint32_t len = (uint32_t)(col_ptr[slab * (Nb + 1) + kb + 1] - col_ptr[slab * (Nb + 1) + kb]);
-      kk = ((uint64_t)(0xFFFFFFFFu - len) << 32) | (uint32_t)item;
-    }
-    key[t] = kk;
-  }
-  __syncthreads();
-  for (int size = 2; size <= kOrderMax; size <<= 1)
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = threadIdx.x; t < kOrderMax / 2; t += 1024) {
-        const int lo = 2 * t - (t & (stride - 1));       // index with bit `stride` clear
-        const int hi = lo + stride;
-        const bool up = (lo & size) == 0;
-        const uint64_t x = key[lo], y = key[hi];
-        if ((x > y) == up) { key[lo] = y; key[hi] = x; }
-      }
-      __syncthreads();
-    }
-  for (int t = threadIdx.x; t < count; t += 1024) order[first + t] = (int32_t)(uint32_t)key[t];
-}
-
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 static size_t order_bytes(const Problem &pb) {
   return round256((size_t)pb.n_slabs * pb.Nb * sizeof(int32_t));
@@ -712,9 +674,8 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   a.order = nullptr;
   {
     const int total = pb.n_slabs * pb.Nb;
-    if (col_ptr && (total + kNumXcd - 1) / kNumXcd <= kOrderMax) {
-      hipLaunchKernelGGL(dkv_order_kernel, dim3(kNumXcd), dim3(1024), 0, st, col_ptr, pb.Nb, total, order);
-      e = hipGetLastError();
+    if (col_ptr && length_order_fits(total)) {
+      e = launch_length_order(col_ptr, pb.Nb, total, order, st);
       if (e != hipSuccess) return e;
       a.order = order;
     }

@@ -65,7 +65,7 @@ hipError_t launch_pool(const Problem &pb, int n, const void *src, const TensorVi
                        hipStream_t st);
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
                       const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
-                      float *lse, hipStream_t st, const GlobalTokens *gt = nullptr);
+                      float *lse, const int32_t *order, hipStream_t st, const GlobalTokens *gt = nullptr);
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
 hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
@@ -85,6 +85,11 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
                       void *dq, void *dk, void *dv, void *workspace, hipStream_t st,
                       const GlobalTokens *gt = nullptr);
 size_t bwd_workspace_bytes(const Problem &pb);
+// order[w] = work item of workgroup slot w: inside each XCD's contiguous share of the
+// total = n_slabs * Nb (slab, block) items, longest list first (ptr = row_ptr or col_ptr of all
+// slabs).  Only where a share holds at most as many items as the sort takes (length_order_fits).
+bool length_order_fits(int total);
+hipError_t launch_length_order(const int32_t *ptr, int Nb, int total, int32_t *order, hipStream_t st);
 size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg);
 
 #ifdef __HIPCC__

@@ -122,6 +122,7 @@ struct FwdArgs {
   // tile count: 0 = this launch takes every slab; +1 = only slabs whose rows hold at least
   // `select_min_tiles` tiles on average; -1 = only the others.
   int select, select_min_tiles;
+  const int32_t *order;   // work item of each workgroup slot (longest row first inside an XCD's share), or null
 };
 
 // does this launch leave the slab to the other kernel?  (wave-uniform; before any barrier)
@@ -164,8 +165,9 @@ __global__ __launch_bounds__(BLK * 2, (BLK == 64 && D == 64) ? 4 : 2) void fwd_k
   bf16 *lds = reinterpret_cast<bf16 *>(smem);
   __shared__ int cols[kMaxNb];
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
-  if (work < 0) return;
+  const int slot = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  if (slot < 0) return;
+  const int work = a.order ? a.order[slot] : slot;
   const int slab = work / a.Nb;
   if (slab_not_mine(a, slab)) return;
   const int qb = work - slab * a.Nb;
@@ -388,8 +390,9 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   const uint32_t ldsV_addr = ldsK_addr + C::kStages * C::kKElems * 2;
   __shared__ uint32_t tabK[kMaxNb + C::kTabPad], tabV[kMaxNb + C::kTabPad];
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
-  if (work < 0) return;
+  const int slot = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  if (slot < 0) return;
+  const int work = a.order ? a.order[slot] : slot;
   const int slab = work / a.Nb;
   if (slab_not_mine(a, slab)) return;
   const int qb = work - slab * a.Nb;
@@ -450,18 +453,15 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   ColTileCopy<BLK, D, C::kGroupWaves> copy_v;
   copy_k.init(wq, lane, a.tk.sL);
   copy_v.init(wq, lane);
-  // false: all copies of a phase by its vector group; true: K copies by the matrix group after
-  // its last MFMA, V copies by the vector group.  Within 2 % of each other (true is ahead on
-  // iid inputs, false on the video-like inputs of the benchmark).
-  constexpr bool kSplitCopies = false;
-  // 2: all copies of a phase by its MATRIX group, one after every few MFMAs, the four wavefronts
-  // of the group staggered by one MFMA each
-#ifndef ASA_FWD_COPY_MODE
-#define ASA_FWD_COPY_MODE 0
+  // The first kMatrixCopies of a phase's copy requests are made by its matrix group behind its
+  // last MFMA (it finishes before the vector group and would wait at the barrier), the rest by
+  // the vector group between blocks of its arithmetic.
+#ifndef ASA_FWD_MATRIX_COPIES
+#define ASA_FWD_MATRIX_COPIES 4   // the K rows (measured 0..4: within 3 % of each other, 4 ahead by 1 %)
 #endif
-  constexpr int kCopyMode = ASA_FWD_COPY_MODE;
   constexpr int kInstrK = RowTileCopy<C::kKT, D, C::kGroupWaves>::kInstr;
   constexpr int kBatchInstr = kInstrK + ColTileCopy<BLK, D, C::kGroupWaves>::kInstr;
+  constexpr int kMatrixCopies = (BLK == 128 && D == 128) ? ASA_FWD_MATRIX_COPIES : 0;
   static_assert(kBatchInstr == 4 || kBatchInstr == 8 || kBatchInstr == 16, "unexpected copy size");
   const int kr = kappa(n), cr = rho(n);
   const int kx = (hl ^ k_swz<D>(kr)) * 8, cx = (hl ^ v_swz(cr)) * 8;
@@ -595,23 +595,13 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   };
   // (idle phases) matrix_slot: this group is the phase's matrix group
   auto dma_idle = [&](auto r_tag, bool matrix_slot) __attribute__((always_inline)) {
-    if (kCopyMode == 2) {
-      if (matrix_slot) {
-        dma_prepare(r_tag);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
-      }
-    } else if (kSplitCopies ? matrix_slot : false) {
+    const int first = matrix_slot ? 0 : kMatrixCopies, last = matrix_slot ? kMatrixCopies : kBatchInstr;
+    if (first < last) {
       dma_prepare(r_tag);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < kInstrK; ++i) dma_one(r_tag, i);
-    } else if (!matrix_slot) {
-      if (!kSplitCopies) dma_prepare(r_tag);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = kSplitCopies ? kInstrK : 0; i < kBatchInstr; ++i) dma_one(r_tag, i);
+      for (int i = 0; i < kBatchInstr; ++i)
+        if (i >= first && i < last) dma_one(r_tag, i);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -630,9 +620,6 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
     bf16x8 ring[kRing];
     int zero = 0;
     if (GT) asm volatile("s_mov_b32 %0, 0" : "=s"(zero));
-    constexpr int kSpacing = (n1 - n0) / kBatchInstr > 0 ? (n1 - n0) / kBatchInstr : 1;
-    const int my_slot = wq % kSpacing;
-    if (kCopyMode == 2) dma_prepare(r_tag);
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
 #pragma unroll
@@ -669,21 +656,16 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
           sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[c_i % kRing], qreg[sk],
                                                             sk == 0 ? zero16 : sacc[mt], 0, 0, 0);
         }
-        if (kCopyMode == 2 && (c_i - n0) / kSpacing < kBatchInstr) {
-          // behind an MFMA the matrix pipe is busy for 32 cycles: a copy request fits there
-          __builtin_amdgcn_sched_barrier(0);
-          if ((c_i - n0) % kSpacing == my_slot) dma_one(r_tag, (c_i - n0) / kSpacing);
-        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_setprio(3);
-    if (kSplitCopies) {
-      // all MFMAs of the phase are issued: request this wavefront's K copies while they drain
+    if (kMatrixCopies > 0) {
+      // all MFMAs of the phase are issued: this wavefront's share of the copy requests
       dma_prepare(r_tag);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < kInstrK; ++i) dma_one(r_tag, i);
+      for (int i = 0; i < kMatrixCopies; ++i) dma_one(r_tag, i);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -695,9 +677,8 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
     constexpr int sb = decltype(rx_tag)::value % C::kSub;
     const Int<(decltype(rx_tag)::value + 1) & 3> r_tag{};   // the phase this runs in
     constexpr int kPortion = kBatchInstr / 8 > 0 ? kBatchInstr / 8 : 1;
-    int next_copy = kSplitCopies ? kInstrK : 0;
+    int next_copy = kMatrixCopies;
     auto request = [&](int n_instr) __attribute__((always_inline)) {
-      if (kCopyMode == 2) return;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int e = 0; e < n_instr; ++e)
@@ -705,7 +686,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
       __builtin_amdgcn_sched_barrier(0);
     };
     __builtin_amdgcn_s_setprio(3);
-    if (!kSplitCopies && kCopyMode != 2) dma_prepare(r_tag);
+    if (kMatrixCopies < kBatchInstr) dma_prepare(r_tag);
     float bias = 0.f;   // added to the scaled scores of pooled keys (log2 domain)
     if (GT && pooled_step(phase_now - 1)) {
       bias = a.bias_log2;
@@ -811,7 +792,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
   f32x4 *xbuf = reinterpret_cast<f32x4 *>(smem);          // [4 * D/32][BLK * 2] f32x4
   float *xm = reinterpret_cast<float *>(xbuf + 4 * (D / 32) * (BLK * 2));
   float *xl = xm + BLK * 2;
-  const int slot = wq * 64 + lane;
+  const int xslot = wq * 64 + lane;
   float l_half = l_run + swap_halves(l_run);
   if (grp == 1) {
 #pragma unroll
@@ -819,15 +800,15 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         f32x4 v = {oacc[dm][4 * q4], oacc[dm][4 * q4 + 1], oacc[dm][4 * q4 + 2], oacc[dm][4 * q4 + 3]};
-        xbuf[(dm * 4 + q4) * (BLK * 2) + slot] = v;
+        xbuf[(dm * 4 + q4) * (BLK * 2) + xslot] = v;
       }
-    xm[slot] = m_run;
-    xl[slot] = l_half;
+    xm[xslot] = m_run;
+    xl[xslot] = l_half;
   }
   __syncthreads();
   if (grp == 1) return;
   {
-    const float m_o = xm[slot], l_o = xl[slot];
+    const float m_o = xm[xslot], l_o = xl[xslot];
     const float m_all = fmaxf(m_run, m_o);
     const float ms = (m_all == -INFINITY) ? 0.f : m_all;
     const float fa = fast_exp2(m_run - ms), fb = fast_exp2(m_o - ms);
@@ -836,7 +817,7 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
     for (int dm = 0; dm < D / 32; ++dm)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 v = xbuf[(dm * 4 + q4) * (BLK * 2) + slot];
+        const f32x4 v = xbuf[(dm * 4 + q4) * (BLK * 2) + xslot];
 #pragma unroll
         for (int e = 0; e < 4; ++e) oacc[dm][4 * q4 + e] = oacc[dm][4 * q4 + e] * fa + v[e] * fb;
       }
@@ -926,8 +907,9 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
 
 hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const void *vt,
                       const int32_t *row_ptr, const int32_t *col_idx, void *o, void *o_lo,
-                      float *lse, hipStream_t st, const GlobalTokens *gt) {
+                      float *lse, const int32_t *order, hipStream_t st, const GlobalTokens *gt) {
   FwdArgs a;
+  a.order = order;
   a.kg = gt ? gt->kg : nullptr;
   a.vgt = gt ? reinterpret_cast<const bf16 *>(gt->vgt) : nullptr;
   a.Lg = gt ? gt->Lg : 0;

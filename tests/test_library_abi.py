@@ -45,7 +45,8 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert rc == -2                                  # d = 96 is not built
     p = binding.Params(B=1, H=2, L=1024, d=64, block=64)
     assert L.asa_attn_fwd(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1   # null pointers
-    assert L.asa_fwd_workspace_bytes(ctypes.byref(p.c())) == 2 * 64 * 1024 * 2
+    # V as transposed tiles, then the order of the forward's workgroups (256-byte granules)
+    assert L.asa_fwd_workspace_bytes(ctypes.byref(p.c())) == 2 * 64 * 1024 * 2 + 256
     assert L.asa_attn_bwd(ctypes.byref(p.c()), *([None] * 15), 0, None) == -1
     assert L.asa_build_mask(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1
     assert L.asa_mask_from_scores(ctypes.byref(p.c()), None, None, None) == -1
