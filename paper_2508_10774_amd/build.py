@@ -25,13 +25,18 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False, extra=()) -> str:
-    """Compile every translation unit and link libasa.so; returns its path."""
+def build_lib(verbose: bool = False, extra=(), lib_path: str = LIB, objdir: str = CSRC,
+              link_extra=()) -> str:
+    """Compile every translation unit and link libasa.so; returns its path.
+
+    extra / link_extra: more hipcc flags for the compile / link lines; lib_path, objdir: where the
+    library and the objects go (the host-sanitizer build of the tests uses a directory of its
+    own, so that the product library is never replaced by an instrumented one)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -50,9 +55,9 @@ def build_lib(verbose: bool = False, extra=()) -> str:
             print(f"--- {src}\n{text}")
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, *objs, "-o", lib_path]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib_path
 
 
 if __name__ == "__main__":

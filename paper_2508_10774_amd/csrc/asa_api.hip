@@ -2,7 +2,12 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
+#include <utility>
+#include <vector>
+
+#include "asa_bench.h"
 
 #include "asa_common.hpp"
 
@@ -26,6 +31,23 @@ void timing_end(hipStream_t st) {
   g_ev_start = nullptr;
   g_ev_stop = nullptr;
 }
+
+hipError_t set_dynamic_lds_once(const void *fn, int bytes) {
+  static std::mutex mu;
+  static std::vector<std::pair<const void *, int>> done;   // (kernel, device) pairs already set
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto &d : done)
+    if (d.first == fn && d.second == dev) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.emplace_back(fn, dev);
+  return e;
+}
+
+static std::atomic<int> g_forced_fwd_kernel{0};
+int forced_fwd_kernel() { return g_forced_fwd_kernel.load(std::memory_order_relaxed); }
 
 static bool view_from(const int64_t st[3], const Problem &pb, TensorView *tv) {
   if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
@@ -122,6 +144,12 @@ const char *asa_error_string(int status) {
 }
 
 const char *asa_last_hip_error(void) { return g_hip_error; }
+
+int asa_test_force_fwd_kernel(int which) {
+  if (which < 0 || which > 2) return ASA_ERR_INVALID_ARG;
+  g_forced_fwd_kernel.store(which, std::memory_order_relaxed);
+  return ASA_OK;
+}
 
 int asa_set_kernel_timing(void *start_event, void *stop_event) {
   if ((start_event == nullptr) != (stop_event == nullptr)) return ASA_ERR_INVALID_ARG;
@@ -496,8 +524,15 @@ int asa_gilbert_order(int32_t T, int32_t Y, int32_t X, int32_t n_prefix, int32_t
 int asa_reorder_tokens(const asa_params *p, int32_t n_tensors, const void *const *src,
                        void *const *dst, const int64_t *src_stride, const int64_t *dst_stride,
                        const int32_t *index, void *hip_stream) {
+  // only B, H, L, d of `p` have a meaning here: the other fields are not looked at
+  if (!p) return ASA_ERR_INVALID_ARG;
+  asa_params shape;
+  memset(&shape, 0, sizeof(shape));
+  shape.B = p->B; shape.H = p->H; shape.L = p->L; shape.d = p->d;
+  shape.block = 128; shape.k_samples = 1; shape.tau = 0.5f; shape.r_max = 1.f;
+  if ((int64_t)p->L > (int64_t)kMaxNb * 128) return ASA_ERR_UNSUPPORTED;
   Problem pb;
-  int rc = resolve(p, &pb);
+  int rc = resolve(&shape, &pb);
   if (rc != ASA_OK) return rc;
   if (n_tensors < 1 || n_tensors > 3 || !src || !dst || !index || !aligned4(index)) return ASA_ERR_INVALID_ARG;
   for (int t = 0; t < n_tensors; ++t) {

@@ -576,24 +576,17 @@ size_t bwd_g_workspace_bytes(const Problem &pb, int Nbg) {
 template <int BLK, int D>
 static hipError_t launch_bwd_t(const BwdArgs &a, const BwdArgs *pooled_launch, hipStream_t st) {
   using C = BwdCfg<BLK, D>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, false, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dq_kernel<BLK, D, true, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDqLds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dkv_kernel<BLK, D>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kDkvLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  {
+    const void *dq_fns[4] = {reinterpret_cast<const void *>(&dq_kernel<BLK, D, false>),
+                             reinterpret_cast<const void *>(&dq_kernel<BLK, D, true>),
+                             reinterpret_cast<const void *>(&dq_kernel<BLK, D, false, true>),
+                             reinterpret_cast<const void *>(&dq_kernel<BLK, D, true, true>)};
+    for (const void *fn : dq_fns) {
+      hipError_t e0 = set_dynamic_lds_once(fn, C::kDqLds);
+      if (e0 != hipSuccess) return e0;
+    }
+    hipError_t e0 = set_dynamic_lds_once(reinterpret_cast<const void *>(&dkv_kernel<BLK, D>), C::kDkvLds);
+    if (e0 != hipSuccess) return e0;
   }
   const int grid = xcd_grid(a.n_slabs * a.Nb);
   hipError_t e = hipSuccess;

@@ -50,6 +50,13 @@ void set_hip_error(hipError_t e);
 void timing_begin(hipStream_t st);
 void timing_end(hipStream_t st);
 
+// hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes), issued once per
+// (kernel, device) under a lock; later calls only look the pair up.
+hipError_t set_dynamic_lds_once(const void *fn, int bytes);
+// Which forward kernel the tests asked for (asa_test_force_fwd_kernel): 0 = the library's own
+// choice, 1 = the lock-step kernel, 2 = the ping-pong kernel.
+int forced_fwd_kernel();
+
 // launchers (each returns a hipError_t from the launch)
 hipError_t launch_transpose(const Problem &pb, const void *src, const TensorView &tv, void *dst,
                             hipStream_t st);

@@ -857,41 +857,36 @@ __global__ __launch_bounds__(BLK * 4, (BLK == 64 && D == 64) ? 2 : 1) void fwd_p
 template <int BLK, int D>
 static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
   using C = FwdCfg<BLK, D>;
+  using P = PpCfg<BLK, D>;
   constexpr int lds = C::kStages * (C::kKElems + C::kVElems) * 2;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_kernel<BLK, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  int grid = xcd_grid(a.n_slabs * a.Nb);
+  const int grid = xcd_grid(a.n_slabs * a.Nb);
   // The ping-pong kernel is the faster one at block = 128, d = 128 (998 vs 914 TFLOP/s at the Wan
   // shape); with smaller blocks or heads its workgroup has too few wavefronts per SIMD or too
-  // little work per phase and the single-stage kernel wins (e.g. 761 vs 511 TFLOP/s at block 64,
+  // little work per phase and the lock-step kernel wins (e.g. 761 vs 511 TFLOP/s at block 64,
   // d 128).  It addresses K tiles by 32-bit byte offsets inside a slab, so slabs of 4 GiB and
-  // more also take the single-stage kernel.  Global tokens exist in the ping-pong kernel only.
-  // ASA_FWD_PLAIN=1 / ASA_FWD_PINGPONG=1 force one or the other (used to compare and test them).
+  // more also take the lock-step kernel.  Global tokens exist in the ping-pong kernel only.
+  // The tests can force one or the other (asa_test_force_fwd_kernel).
   const bool fits32 = (uint64_t)a.Nb * BLK * (uint64_t)a.tk.sL * 2u < 0xFFFFFFFFull;
   if (a.Nbg > 0 && (!fits32 || a.Nb + a.Nbg > kMaxNb || a.tk.sL != D)) return hipErrorNotSupported;
-  const bool prefer_pp = (BLK == 128 && D == 128 && !getenv("ASA_FWD_PLAIN")) || getenv("ASA_FWD_PINGPONG");
+  const int forced = forced_fwd_kernel();
+  const bool prefer_pp = forced == 2 || (forced == 0 && BLK == 128 && D == 128);
   FwdArgs b = a;
   b.select = 0;
   hipError_t e = hipSuccess;
-  // no lists (dense): every row holds Nb tiles, the same choice is made here
-  const bool dense_short = !a.row_ptr && a.Nbg == 0 && a.select_min_tiles > 0 &&
-                           a.Nb < a.select_min_tiles && !getenv("ASA_FWD_PINGPONG");
+  // Short lists: the ping-pong kernel costs ~8 us per workgroup around its steady state, the
+  // lock-step kernel ~3 us; they cross at 16-20 tiles per row.  The host cannot see the lists, so
+  // with lists BOTH kernels are launched and each workgroup leaves at once if its (batch, head)
+  // slab's tile count belongs to the other kernel (the launch that finds nothing to do costs
+  // 4-10 us).  Without lists (dense) every row holds Nb tiles and the choice is made here.
+  constexpr int kPingPongMinTiles = 18;
+  b.select_min_tiles = kPingPongMinTiles;
+  const bool dense_short = !a.row_ptr && a.Nbg == 0 && a.Nb < kPingPongMinTiles && forced == 0;
   if (fits32 && (a.Nbg > 0 || prefer_pp) && !dense_short) {
-    using P = PpCfg<BLK, D>;
-    // Short lists: the ping-pong kernel costs ~8 us per workgroup around its steady state, the
-    // lock-step kernel ~3 us; they cross at 16-20 tiles per row.  Where the rule's lower clamp
-    // does not already promise long rows, both kernels are launched and each takes the slabs
-    // that suit it (the host cannot see the lists).  ASA_FWD_PINGPONG forces one launch.
-    const bool both = a.select_min_tiles > 0 && a.Nbg == 0 && a.row_ptr && !getenv("ASA_FWD_PINGPONG");
+    const bool both = a.Nbg == 0 && a.row_ptr && forced == 0;
     if (both) b.select = 1;
     const void *fn = a.Nbg > 0 ? reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, true>)
                                : reinterpret_cast<const void *>(&fwd_pp_kernel<BLK, D, false>);
-    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, P::kLdsBytes);
+    e = set_dynamic_lds_once(fn, P::kLdsBytes);
     if (e != hipSuccess) return e;
     if (a.Nbg > 0)
       hipLaunchKernelGGL((fwd_pp_kernel<BLK, D, true>), dim3(grid), dim3(P::kThreads), P::kLdsBytes, st, b);
@@ -901,6 +896,8 @@ static hipError_t launch_fwd_t(const FwdArgs &a, hipStream_t st) {
     if (e != hipSuccess || !both) return e;
     b.select = -1;
   }
+  e = set_dynamic_lds_once(reinterpret_cast<const void *>(&fwd_kernel<BLK, D>), lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((fwd_kernel<BLK, D>), dim3(grid), dim3(C::kThreads), lds, st, b);
   return hipGetLastError();
 }
@@ -920,10 +917,8 @@ hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const voi
   a.tq = pb.q; a.tk = pb.k; a.to = pb.o;
   a.H = pb.H; a.L = pb.L; a.Lpad = pb.Lpad; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs;
   a.scale_log2e = pb.scale * 1.44269504088896340736f;
-  // rows hold at least m_min tiles when the lists come from the rule: no choice to make then
-  constexpr int kPingPongMinTiles = 18;
   a.select = 0;
-  a.select_min_tiles = pb.m_min >= kPingPongMinTiles ? 0 : kPingPongMinTiles;
+  a.select_min_tiles = 0;
   if (pb.block == 128 && pb.d == 128) return launch_fwd_t<128, 128>(a, st);
   if (pb.block == 128 && pb.d == 64) return launch_fwd_t<128, 64>(a, st);
   if (pb.block == 64 && pb.d == 128) return launch_fwd_t<64, 128>(a, st);

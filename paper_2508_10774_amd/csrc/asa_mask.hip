@@ -330,17 +330,11 @@ hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *
   const int n_groups = (pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
   const int grid = xcd_grid(pb.n_slabs * n_groups);
   const int lds = 2 * kProbeKBlocks * 16 * pb.d * 2;   // two chunks of sampled key rows
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       2 * kProbeKBlocks * 16 * 128 * 2);
+  if (pb.d == 128) {
+    const void *fn = table ? reinterpret_cast<const void *>(&probe_kernel<128, true>)
+                           : reinterpret_cast<const void *>(&probe_kernel<128, false>);
+    hipError_t e = set_dynamic_lds_once(fn, 2 * kProbeKBlocks * 16 * 128 * 2);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_kernel<128, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * kProbeKBlocks * 16 * 128 * 2);
-    if (e != hipSuccess) return e;
-    attr_set = true;
   }
   if (pb.d == 128 && table)
     hipLaunchKernelGGL((probe_kernel<128, true>), dim3(grid), dim3(512), lds, st, a);

@@ -12,15 +12,13 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True, params=["auto", "pingpong"])
-def kernel_choice(request, monkeypatch):
+def kernel_choice(request):
     """Every test of this module runs twice: with the library's own choice of forward kernel (short
     lists go to the lock-step kernel) and with the ping-pong kernel forced, so that both kernels
     see every edge case."""
-    if request.param == "pingpong":
-        monkeypatch.setenv("ASA_FWD_PINGPONG", "1")
-    else:
-        monkeypatch.delenv("ASA_FWD_PINGPONG", raising=False)
-    return request.param
+    binding.asa_test_force_fwd_kernel(2 if request.param == "pingpong" else 0)
+    yield request.param
+    binding.asa_test_force_fwd_kernel(0)
 
 
 def _case(B, H, L, d, block, seed):
@@ -96,10 +94,9 @@ def test_fwd_dense_specialisation_needs_no_lists(L, d, block):
     util.assert_close_bf16(util.host_f32(o), want, "dense O")
 
 
-def test_fwd_single_stage_kernel_is_still_correct(monkeypatch):
+def test_fwd_single_stage_kernel_is_still_correct():
     """The kernel that takes over for slabs of 4 GiB and more, forced by its switch."""
-    monkeypatch.delenv("ASA_FWD_PINGPONG", raising=False)
-    monkeypatch.setenv("ASA_FWD_PLAIN", "1")
+    binding.asa_test_force_fwd_kernel(1)
     p = binding.Params(B=1, H=2, L=1000, d=128, block=128)
     qb, kb, vb = _case(1, 2, 1000, 128, 128, seed=5)
     mask = synth.random_block_mask(p.Nb, 0.5, seed=5, slabs=2)
@@ -110,8 +107,8 @@ def test_fwd_single_stage_kernel_is_still_correct(monkeypatch):
 
 
 @pytest.mark.parametrize("L,d,block", [(1024, 64, 64), (520, 128, 64), (300, 64, 128)])
-def test_fwd_ping_pong_kernel_at_the_sizes_where_it_is_not_the_default(monkeypatch, L, d, block):
-    monkeypatch.setenv("ASA_FWD_PINGPONG", "1")
+def test_fwd_ping_pong_kernel_at_the_sizes_where_it_is_not_the_default(L, d, block):
+    binding.asa_test_force_fwd_kernel(2)
     p = binding.Params(B=1, H=2, L=L, d=d, block=block)
     qb, kb, vb = _case(1, 2, L, d, block, seed=L)
     _check_fwd(p, qb, kb, vb, synth.random_block_mask(p.Nb, 0.5, seed=L, slabs=2))

@@ -11,10 +11,13 @@ from paper_2508_10774_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "asa.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(asa_[a-z_]+)\s*\(", text)))
+def _declared(headers=("asa.h", "asa_bench.h")):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(asa_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_entry_points():
@@ -23,6 +26,10 @@ def test_header_declares_the_entry_points():
                  "asa_mask_from_scores"):
         assert must in names
     assert sorted(binding.EXPORTS) == names
+    # benchmark / test tooling is declared apart from the product interface
+    product = _declared(("asa.h",))
+    for tool in ("asa_mfma_rate_probe", "asa_set_kernel_timing", "asa_test_force_fwd_kernel"):
+        assert tool not in product and tool in names
 
 
 def test_library_exports_every_declared_symbol():
