@@ -161,9 +161,8 @@ int asa_set_kernel_timing(void *start_event, void *stop_event) {
 size_t asa_mask_workspace_bytes(const asa_params *p) {
   Problem pb;
   if (resolve(p, &pb) != ASA_OK) return 0;
-  // the probe's per-row block maxima, then the importance map (used when the caller does not
-  // ask for it)
-  return probe_workspace_bytes(pb) + round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
+  // the probe's per-row block maxima and soft-max statistics
+  return round256(probe_workspace_bytes(pb));
 }
 
 static size_t fwd_order_bytes(const Problem &pb) {
@@ -203,7 +202,6 @@ static int build_mask_impl(const asa_params *p, const uint64_t *seed, const void
   if (!workspace || workspace_bytes < base + (seed ? table_bytes(pb) : 0) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
-  float *scores = p_imp ? p_imp : reinterpret_cast<float *>(ws + probe_workspace_bytes(pb));
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   uint8_t *table = nullptr;
   if (seed) {
@@ -212,10 +210,10 @@ static int build_mask_impl(const asa_params *p, const uint64_t *seed, const void
     if (e0 != hipSuccess) return finish(e0);
   }
   timing_begin(st);
-  hipError_t e = launch_probe(pb, q, k, scores, workspace, st, table);
+  hipError_t e = launch_probe(pb, q, k, workspace, st, table);
   timing_end(st);
   if (e != hipSuccess) return finish(e);
-  e = launch_rule(pb, scores, mask, st);
+  e = launch_finish_rule(pb, workspace, p_imp, mask, table, st);
   if (e != hipSuccess) return finish(e);
   return finish(launch_csr(pb, mask, row_ptr, col_idx, col_ptr, row_idx, st));
 }

@@ -75,8 +75,12 @@ hipError_t launch_fwd(const Problem &pb, const void *q, const void *k, const voi
                       float *lse, const int32_t *order, hipStream_t st, const GlobalTokens *gt = nullptr);
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st);
-hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
-                        void *rt_workspace, hipStream_t st, const uint8_t *table = nullptr);
+// first sweep of the probe (block-row maxima and soft-max statistics into the workspace) ...
+hipError_t launch_probe(const Problem &pb, const void *q, const void *k, void *workspace,
+                        hipStream_t st, const uint8_t *table = nullptr);
+// ... and its second sweep fused with the rule: P_imp rows (written if p_imp is not null) -> mask
+hipError_t launch_finish_rule(const Problem &pb, void *workspace, float *p_imp, uint8_t *mask,
+                              const uint8_t *table, hipStream_t st);
 int gilbert_order(int T, int Y, int X, int n_prefix, int32_t *order, int32_t *inverse);  // asa_status; host
 hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *src, void *const *dst,
                           const TensorView &ts, const TensorView &td, const int32_t *index,

@@ -12,8 +12,8 @@ namespace asa {
 // soft-max (over ALL sampled keys of the slab) of scale * Qs Ks^T.
 //
 // Alg. 1 of the paper, reorganised for 64-wide wavefronts.  A workgroup of 8 wavefronts owns 8
-// query blocks and sweeps the key blocks of its slab: wavefronts w and w + 4 share two query
-// blocks and split every chunk of key blocks between them.  The sampled key rows (Alg. 2
+// query blocks and sweeps one of kProbeKeySplits ranges of the key blocks of its slab:
+// wavefronts w and w + 4 share two query blocks and split every chunk of key blocks between them.  The sampled key rows (Alg. 2
 // steps 1-3) are gathered from K by direct global->LDS loads, 8 key blocks (128 rows) per
 // chunk, double-buffered and shared by all wavefronts.  One chain of 32x32x16
 // bf16 MFMAs gives a 32 x 32 logit tile: 2 key blocks x 16 samples on the M axis, 2 query
@@ -23,14 +23,16 @@ namespace asa {
 // the row is kept lane-locally over the key blocks of that parity and merged across the two
 // halves (and the two wavefronts of a pair) once, at the end.  No cross-lane traffic inside the
 // sweep; the exponentials of a tile depend only on that tile's own maximum (Alg. 1 steps 12-14),
-// so consecutive tiles overlap.  Rt goes to a workspace in
-// global memory (it stays in L2); a second sweep turns it into probabilities and max-pools
-// over the sampled rows.
+// so consecutive tiles overlap.  Rt and each wavefront's (maximum, denominator) pair go to a
+// workspace in global memory; finish_rule_kernel merges the pairs of a sampled row, turns Rt
+// into probabilities, max-pools over the sampled rows and applies the rule to the row.
 // ---------------------------------------------------------------------------------------
 struct ProbeArgs {
   const void *q, *k;
   float *p_imp;
-  float *rt;         // workspace [work item][wave][Nb rounded up to 8][32]
+  float *rt;         // workspace [query group][pair][Nb rounded up to 8][32]: block-row maxima
+  float *stat_m;     // workspace [work item][wave][32]: running maximum of the wavefront's keys
+  double *stat_l;    //           and the matching denominator
   TensorView tq, tk;
   int H, L, Nb, n_slabs, block, ks;
   int n_valid_last;  // sampled tokens of the last block that lie below L
@@ -41,6 +43,10 @@ struct ProbeArgs {
 
 constexpr int kProbeQBlocks = 8;   // query blocks per workgroup
 constexpr int kProbeKBlocks = 8;   // key blocks per LDS chunk
+// The key blocks of a slab are cut into this many ranges, one workgroup each: at the Wan2.1 shape
+// 12 heads x 32 query groups x 2 = 768 workgroups, three per compute unit (one range per group
+// gave 384 workgroups for 512 resident slots: half of the compute units carried twice the load).
+constexpr int kProbeKeySplits = 2;
 
 typedef __attribute__((address_space(3))) void lds_void_m;
 __device__ __forceinline__ void probe_dma16(const void *src, void *lds_dst) {
@@ -65,12 +71,12 @@ __global__ __launch_bounds__(512, 4) void probe_kernel(ProbeArgs a) {   // (4 wa
   constexpr int DMA_PER_WAVE = ROWS * CH / 64 / 8;  // 1 KB per wave instruction, 8 wavefronts
   extern __shared__ __align__(1024) unsigned char probe_smem[];
   bf16 (*Kc)[ROWS * D] = reinterpret_cast<bf16 (*)[ROWS * D]>(probe_smem);   // two buffers
-  __shared__ float sM[8][32];    // per wavefront: running maximum of its share of the keys
-  __shared__ double sL[8][32];   //                and the matching denominator
 
   const int n_groups = (a.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * n_groups);
-  if (work < 0) return;
+  const int item = xcd_contiguous_work(blockIdx.x, a.n_slabs * n_groups * kProbeKeySplits);
+  if (item < 0) return;
+  const int work = item / kProbeKeySplits;          // (slab, query group)
+  const int split = item - work * kProbeKeySplits;  // which range of key blocks
   const int slab = work / n_groups;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -243,22 +249,25 @@ __global__ __launch_bounds__(512, 4) void probe_kernel(ProbeArgs a) {   // (4 wa
     for (int sb = 0; sb < kProbeKBlocks / 4; ++sb) rt_c[rt_off + sb * 64] = rt_pend[sb];
   };
   const int n_chunks = nb_pad / kProbeKBlocks;
-  fetch_any(0, 0);
-  for (int chunk = 0; chunk < n_chunks; chunk += 2) {
+  const int per_split = (n_chunks + kProbeKeySplits - 1) / kProbeKeySplits;
+  const int c0 = min(n_chunks, split * per_split), c1 = min(n_chunks, c0 + per_split);   // my chunks
+  if (c0 < c1) fetch_any(c0, 0);
+  for (int chunk = c0; chunk < c1; chunk += 2) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): my loads of this chunk have landed
     __syncthreads();                     // everyone's have, and the other buffer is free
-    if (chunk > 0) store_rt(chunk - 1);
-    if (chunk + 1 < n_chunks) fetch_any(chunk + 1, 1);
+    if (chunk > c0) store_rt(chunk - 1);
+    if (chunk + 1 < c1) fetch_any(chunk + 1, 1);
     sweep_chunk(chunk, std::integral_constant<int, 0>{});
-    if (chunk + 1 >= n_chunks) break;
+    if (chunk + 1 >= c1) break;
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     store_rt(chunk);
-    if (chunk + 2 < n_chunks) fetch_any(chunk + 2, 0);
+    if (chunk + 2 < c1) fetch_any(chunk + 2, 0);
     sweep_chunk(chunk + 1, std::integral_constant<int, 1>{});
   }
-  store_rt(n_chunks - 1);
-  // merge the two parities of each query
+  if (c0 < c1) store_rt(c1 - 1);
+  // merge the two parities of each query; the pair (maximum, denominator) of this wavefront's
+  // share of the keys goes to the workspace (the kernel that follows merges the shares)
   {
     const float Mo = __shfl_xor(Mt, 32, 64);
     const double lo = __shfl_xor(lt, 32, 64);
@@ -266,69 +275,47 @@ __global__ __launch_bounds__(512, 4) void probe_kernel(ProbeArgs a) {   // (4 wa
     const float Ms = (Mall == -INFINITY) ? 0.f : Mall;
     const double lall = (double)__expf(Mt - Ms) * lt + (double)__expf(Mo - Ms) * lo;
     if (hl == 0) {
-      sM[wave][n] = Mall;
-      sL[wave][n] = lall;
-    }
-  }
-  __syncthreads();   // also makes the wavefronts' Rt stores visible to the whole workgroup
-
-  // second sweep: wavefront w finishes query block i_base + w
-  {
-    const int i = i_base + wave;
-    if (i >= a.Nb) return;
-
-    const int pr_ = wave >> 1, qb = wave & 1;           // its pair and position in the pair
-    const float *rtq = a.rt + ((int64_t)work * 4 + pr_) * nb_pad * 32 + qb * 16;
-    // merge the two wavefronts of the pair
-    // (the denominator is summed in fp64; its reciprocal is rounded to fp32 once per sampled
-    // row: the exponentials below are fp32 anyway)
-    float Mrow[16], Linv[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const float m0 = sM[pr_][qb * 16 + u], m1 = sM[pr_ + 4][qb * 16 + u];
-      const float mm = fmaxf(m0, m1);
-      const float ms = (mm == -INFINITY) ? 0.f : mm;
-      Mrow[u] = mm;
-      Linv[u] = (float)(1.0 / ((double)__expf(m0 - ms) * sL[pr_][qb * 16 + u] +
-                               (double)__expf(m1 - ms) * sL[pr_ + 4][qb * 16 + u]));
-    }
-    const int rows_ok = valid_in_block(i);
-    float *out = a.p_imp + ((int64_t)slab * a.Nb + i) * a.Nb;
-    for (int j = lane; j < a.Nb; j += 64) {
-      const f32x4 *src = reinterpret_cast<const f32x4 *>(rtq + j * 32);
-      const f32x4 r0 = src[0], r1 = src[1], r2 = src[2], r3 = src[3];
-      const float rv[16] = {r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3],
-                            r2[0], r2[1], r2[2], r2[3], r3[0], r3[1], r3[2], r3[3]};
-      float best = 0.f;
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        if (u < rows_ok && rv[u] != -INFINITY) best = fmaxf(best, __expf(rv[u] - Mrow[u]) * Linv[u]);
-      }
-      out[j] = best;
+      a.stat_m[((int64_t)item * 8 + wave) * 32 + n] = Mall;
+      a.stat_l[((int64_t)item * 8 + wave) * 32 + n] = lall;
     }
   }
 }
 
-size_t probe_workspace_bytes(const Problem &pb) {
+static size_t probe_rt_bytes(const Problem &pb) {
   const size_t n_groups = (pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
   const size_t nb_pad = (pb.Nb + kProbeKBlocks - 1) / kProbeKBlocks * kProbeKBlocks;
   return ((size_t)pb.n_slabs * n_groups * 4 * nb_pad * 32 * sizeof(float) + 255) & ~(size_t)255;
 }
+static size_t probe_items(const Problem &pb) {
+  return (size_t)pb.n_slabs * ((pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks) * kProbeKeySplits;
+}
+size_t probe_workspace_bytes(const Problem &pb) {
+  // block-row maxima, then the per-wavefront soft-max statistics (fp64 denominators first)
+  return probe_rt_bytes(pb) + probe_items(pb) * 8 * 32 * (sizeof(double) + sizeof(float));
+}
 
-hipError_t launch_probe(const Problem &pb, const void *q, const void *k, float *p_imp,
-                        void *rt_workspace, hipStream_t st, const uint8_t *table) {
-  ProbeArgs a;
-  a.table = table;
-  a.q = q; a.k = k; a.p_imp = p_imp; a.rt = reinterpret_cast<float *>(rt_workspace);
-  a.tq = pb.q; a.tk = pb.k;
-  a.H = pb.H; a.L = pb.L; a.Nb = pb.Nb; a.n_slabs = pb.n_slabs; a.block = pb.block; a.ks = pb.ks;
-  a.scale = pb.scale;
-  for (int u = 0; u < kMaxSamples; ++u) a.offs[u] = pb.offs[u];
-  a.n_valid_last = 0;
+static void fill_probe_args(const Problem &pb, const void *q, const void *k, float *p_imp,
+                            void *workspace, const uint8_t *table, ProbeArgs *a) {
+  a->table = table;
+  a->q = q; a->k = k; a->p_imp = p_imp;
+  unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+  a->rt = reinterpret_cast<float *>(ws);
+  a->stat_l = reinterpret_cast<double *>(ws + probe_rt_bytes(pb));
+  a->stat_m = reinterpret_cast<float *>(ws + probe_rt_bytes(pb) + probe_items(pb) * 8 * 32 * sizeof(double));
+  a->tq = pb.q; a->tk = pb.k;
+  a->H = pb.H; a->L = pb.L; a->Nb = pb.Nb; a->n_slabs = pb.n_slabs; a->block = pb.block; a->ks = pb.ks;
+  a->scale = pb.scale;
+  for (int u = 0; u < kMaxSamples; ++u) a->offs[u] = pb.offs[u];
+  a->n_valid_last = 0;
   for (int u = 0; u < pb.ks; ++u)
-    if ((int64_t)(pb.Nb - 1) * pb.block + pb.offs[u] < pb.L) ++a.n_valid_last;
-  const int n_groups = (pb.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
-  const int grid = xcd_grid(pb.n_slabs * n_groups);
+    if ((int64_t)(pb.Nb - 1) * pb.block + pb.offs[u] < pb.L) ++a->n_valid_last;
+}
+
+hipError_t launch_probe(const Problem &pb, const void *q, const void *k, void *workspace,
+                        hipStream_t st, const uint8_t *table) {
+  ProbeArgs a;
+  fill_probe_args(pb, q, k, nullptr, workspace, table, &a);
+  const int grid = xcd_grid((int)probe_items(pb));
   const int lds = 2 * kProbeKBlocks * 16 * pb.d * 2;   // two chunks of sampled key rows
   if (pb.d == 128) {
     const void *fn = table ? reinterpret_cast<const void *>(&probe_kernel<128, true>)
@@ -426,26 +413,15 @@ __device__ __forceinline__ float key_score(uint32_t k) {
   return __uint_as_float(u);
 }
 
-// Four rows per workgroup, one per wavefront: every step below is wave-synchronous, so there
-// are no workgroup barriers, and the sequential running sums of different rows run on
-// different SIMDs.
+// The rule on one row whose Nb scores sit in the wavefront's registers as sort keys, in any
+// order (key = order image of the score in the high word, block index in the low word; slots
+// beyond Nb hold ~0).  cum: NPAD doubles of LDS owned by this wavefront.  Every step is
+// wave-synchronous: no workgroup barrier.  Writes the row's Nb mask bytes to dst.
 template <int NPAD>
-__global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
+__device__ __forceinline__ void rule_on_keys(unsigned long long (&key)[NPAD / 64], double *cum, int lane,
+                                             int i, int Nb, float tau, int m_min, int m_max,
+                                             int n_prefix_blocks, uint8_t *dst) {
   constexpr int E = NPAD / 64;               // keys per lane; rank of key r of a lane = lane * E + r
-  __shared__ double cum_all[4][NPAD];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + wave;          // slab * Nb + i
-  if (row >= a.n_rows) return;                     // whole wavefront; no workgroup barriers below
-  double *cum = cum_all[wave];
-  const int i = row % a.Nb;
-  const float *src = a.scores + (int64_t)row * a.Nb;
-  unsigned long long key[E];
-#pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int j = lane * E + r;
-    key[r] = j < a.Nb ? (((unsigned long long)desc_key(src[j]) << 32) | (unsigned)j)
-                      : ~0ull;        // padding sorts last
-  }
   // ascending bitonic network over e = lane * E + r: stage (k, jj) orders the pair (e, e ^ jj)
   // upwards where (e & k) == 0 and downwards elsewhere
   for (int k = 2; k <= NPAD; k <<= 1) {
@@ -484,7 +460,7 @@ __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int e = lane * E + r;
-    cum[e] = e < a.Nb ? (double)key_score((uint32_t)(key[r] >> 32)) : 0.0;
+    cum[e] = e < Nb ? (double)key_score((uint32_t)(key[r] >> 32)) : 0.0;
   }
   __builtin_amdgcn_wave_barrier();
   // Running sums in place: cum[r] becomes c_{r+1} = sum of the r+1 best scores.  Sequential on
@@ -492,7 +468,7 @@ __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
   // sit on the dependent chain.
   if (lane == 0) {
     double c = 0.0;
-    for (int r0 = 0; r0 < a.Nb; r0 += 8) {
+    for (int r0 = 0; r0 < Nb; r0 += 8) {
       double v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = cum[r0 + u];
@@ -506,27 +482,148 @@ __global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
     }
   }
   __builtin_amdgcn_wave_barrier();
-  const double thr = (double)a.tau * cum[a.Nb - 1];   // tau * T
+  const double thr = (double)tau * cum[Nb - 1];   // tau * T
   int inside = 0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int e = lane * E + r;
-    if (e < a.Nb) inside += ((e == 0 ? 0.0 : cum[e - 1]) < thr);
+    if (e < Nb) inside += ((e == 0 ? 0.0 : cum[e - 1]) < thr);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) inside += __shfl_xor(inside, off, 64);
   int m = inside;
-  m = m < a.m_min ? a.m_min : m;
-  m = m > a.m_max ? a.m_max : m;
-  uint8_t *dst = a.mask + (int64_t)row * a.Nb;
+  m = m < m_min ? m_min : m;
+  m = m > m_max ? m_max : m;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int e = lane * E + r;
-    if (e < a.Nb) {
+    if (e < Nb) {
       const int j = (int)(key[r] & 0xffffffffu);
-      dst[j] = (e < m) || (i < a.n_prefix_blocks) || (j < a.n_prefix_blocks);
+      dst[j] = (e < m) || (i < n_prefix_blocks) || (j < n_prefix_blocks);
     }
   }
+}
+
+// Four rows per workgroup, one per wavefront, so that the sequential running sums of different
+// rows run on different SIMDs.
+template <int NPAD>
+__global__ __launch_bounds__(256) void rule_kernel(RuleArgs a) {
+  constexpr int E = NPAD / 64;
+  __shared__ double cum_all[4][NPAD];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;          // slab * Nb + i
+  if (row >= a.n_rows) return;                     // whole wavefront; no workgroup barriers below
+  const float *src = a.scores + (int64_t)row * a.Nb;
+  unsigned long long key[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int j = lane * E + r;
+    key[r] = j < a.Nb ? (((unsigned long long)desc_key(src[j]) << 32) | (unsigned)j)
+                      : ~0ull;        // padding sorts last
+  }
+  rule_on_keys<NPAD>(key, cum_all[wave], lane, row % a.Nb, a.Nb, a.tau, a.m_min, a.m_max,
+                     a.n_prefix_blocks, a.mask + (int64_t)row * a.Nb);
+}
+
+// ---------------------------------------------------------------------------------------
+// Second half of the probe (Alg. 1, second loop) fused with the rule: one wavefront per query
+// block.  It merges the soft-max statistics of the wavefronts that swept this block's sampled
+// rows (two halves of every chunk x the ranges of key blocks), turns the block-row maxima into
+// probabilities, max-pools them over the sampled rows -- the row P_imp[i][:], written out if the
+// caller wants it -- and applies the rule to that row while it is still in registers.
+// ---------------------------------------------------------------------------------------
+template <int NPAD>
+__global__ __launch_bounds__(256) void finish_rule_kernel(ProbeArgs a, RuleArgs ra) {
+  constexpr int E = NPAD / 64;
+  __shared__ double cum_all[4][NPAD];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;          // slab * Nb + i
+  if (row >= ra.n_rows) return;
+  const int slab = row / a.Nb, i = row - slab * a.Nb;
+  const int n_groups = (a.Nb + kProbeQBlocks - 1) / kProbeQBlocks;
+  const int nb_pad = (a.Nb + kProbeKBlocks - 1) / kProbeKBlocks * kProbeKBlocks;
+  const int work = slab * n_groups + i / kProbeQBlocks;      // the query group that swept this block
+  const int w = i % kProbeQBlocks, pr_ = w >> 1, qb = w & 1;  // its pair and position in the pair
+  const float *rtq = a.rt + ((int64_t)work * 4 + pr_) * nb_pad * 32 + qb * 16;
+  // merge the shares: wavefronts pr_ and pr_ + 4 of every key range
+  // (the denominator is summed in fp64; its reciprocal is rounded to fp32 once per sampled
+  // row: the exponentials below are fp32 anyway)
+  // Lane u < 16 merges the shares of sampled row u; the 16 results are then handed to every
+  // lane through scalar registers (all lanes doing all 16 rows cost 16 fp64 divisions a lane).
+  float my_m = -INFINITY, my_inv = 0.f;
+  {
+    const int u = lane & 15;
+    float pm[2 * kProbeKeySplits];
+    double pl[2 * kProbeKeySplits];
+#pragma unroll
+    for (int sp = 0; sp < kProbeKeySplits; ++sp)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int64_t at = (((int64_t)work * kProbeKeySplits + sp) * 8 + pr_ + 4 * hf) * 32 + qb * 16 + u;
+        pm[2 * sp + hf] = a.stat_m[at];
+        pl[2 * sp + hf] = a.stat_l[at];
+        my_m = fmaxf(my_m, pm[2 * sp + hf]);
+      }
+    const float ms = (my_m == -INFINITY) ? 0.f : my_m;
+    double l = 0.0;
+#pragma unroll
+    for (int x = 0; x < 2 * kProbeKeySplits; ++x) l += (double)__expf(pm[x] - ms) * pl[x];
+    my_inv = (float)(1.0 / l);
+  }
+  float Mrow[16], Linv[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    Mrow[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_m), u));
+    Linv[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_inv), u));
+  }
+  int rows_ok = a.ks;                       // sampled rows of this block that lie below L
+  if (i == a.Nb - 1) {
+    if (a.table) {
+      rows_ok = 0;
+      const uint8_t *t = a.table + ((int64_t)slab * a.Nb + i) * a.ks;
+      for (int u = 0; u < a.ks; ++u) rows_ok += (int64_t)i * a.block + t[u] < a.L;
+    } else {
+      rows_ok = a.n_valid_last;
+    }
+  }
+  float *out = a.p_imp ? a.p_imp + (int64_t)row * a.Nb : nullptr;
+  unsigned long long key[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int j = lane + 64 * r;
+    key[r] = ~0ull;                         // padding sorts last
+    if (j < a.Nb) {
+      const f32x4 *src = reinterpret_cast<const f32x4 *>(rtq + (int64_t)j * 32);
+      const f32x4 r0 = src[0], r1 = src[1], r2 = src[2], r3 = src[3];
+      const float rv[16] = {r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3],
+                            r2[0], r2[1], r2[2], r2[3], r3[0], r3[1], r3[2], r3[3]};
+      float best = 0.f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        if (u < rows_ok && rv[u] != -INFINITY) best = fmaxf(best, __expf(rv[u] - Mrow[u]) * Linv[u]);
+      }
+      if (out) out[j] = best;
+      key[r] = ((unsigned long long)desc_key(best) << 32) | (unsigned)j;
+    }
+  }
+  rule_on_keys<NPAD>(key, cum_all[wave], lane, i, a.Nb, ra.tau, ra.m_min, ra.m_max, ra.n_prefix_blocks,
+                     ra.mask + (int64_t)row * a.Nb);
+}
+
+hipError_t launch_finish_rule(const Problem &pb, void *workspace, float *p_imp, uint8_t *mask,
+                              const uint8_t *table, hipStream_t st) {
+  ProbeArgs a;
+  fill_probe_args(pb, nullptr, nullptr, p_imp, workspace, table, &a);
+  RuleArgs ra;
+  ra.scores = nullptr; ra.mask = mask; ra.Nb = pb.Nb; ra.m_min = pb.m_min; ra.m_max = pb.m_max;
+  ra.n_prefix_blocks = pb.n_prefix_blocks; ra.tau = pb.tau;
+  ra.n_rows = pb.n_slabs * pb.Nb;
+  const dim3 grid((ra.n_rows + 3) / 4), block(256);
+  if (pb.Nb <= 128) hipLaunchKernelGGL(finish_rule_kernel<128>, grid, block, 0, st, a, ra);
+  else if (pb.Nb <= 256) hipLaunchKernelGGL(finish_rule_kernel<256>, grid, block, 0, st, a, ra);
+  else if (pb.Nb <= 512) hipLaunchKernelGGL(finish_rule_kernel<512>, grid, block, 0, st, a, ra);
+  else hipLaunchKernelGGL(finish_rule_kernel<1024>, grid, block, 0, st, a, ra);
+  return hipGetLastError();
 }
 
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st) {
@@ -615,8 +712,89 @@ __global__ __launch_bounds__(128) void csr_fill_kernel(const uint8_t *mask, int 
   }
 }
 
+// The same in ONE kernel where a slab's mask fits in LDS (Nb <= 384).  kCsrParts workgroups per
+// slab; each holds the whole mask (rows padded by 4 bytes, so that a walk down a column meets
+// every bank once), counts every row and column (one thread each), scans the counts in a single
+// wavefront and then fills its share of the lists (one wavefront per row or column, ballot
+// compaction, so the lists come out ascending and the stores are coalesced).  The counting is
+// repeated by every part of a slab: cheaper than a second launch and a trip through memory.
+constexpr int kCsrLdsMaxNb = 384;
+constexpr int kCsrParts = 16;
+__global__ __launch_bounds__(1024) void csr_slab_kernel(const uint8_t *mask, int Nb, int32_t *row_ptr,
+                                                        int32_t *col_idx, int32_t *col_ptr,
+                                                        int32_t *row_idx) {
+  extern __shared__ __align__(16) unsigned char csr_smem[];
+  __shared__ int cnt[2][kCsrLdsMaxNb + 1];        // row counts, column counts -> exclusive offsets
+  const int part = blockIdx.x, slab = blockIdx.y, tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int pitch = Nb + 4;
+  const uint8_t *m = mask + (int64_t)slab * Nb * Nb;
+  if ((Nb & 3) == 0 && (reinterpret_cast<uintptr_t>(mask) & 3) == 0) {   // four entries at a time
+    const uint32_t *m4 = reinterpret_cast<const uint32_t *>(m);
+    for (int t = tid; t < Nb * Nb / 4; t += 1024) {
+      const int e = 4 * t;
+      *reinterpret_cast<uint32_t *>(csr_smem + (e / Nb) * pitch + (e % Nb)) = m4[t];
+    }
+  } else {
+    for (int t = tid; t < Nb * Nb; t += 1024) csr_smem[(t / Nb) * pitch + (t % Nb)] = m[t];
+  }
+  __syncthreads();
+  const int n_dir = col_ptr ? 2 : 1;
+  if (tid < n_dir * Nb) {                          // thread = one row (dir 0) or one column (dir 1)
+    const int dir = tid / Nb, i = tid - dir * Nb;
+    const unsigned char *src = csr_smem + (dir == 0 ? i * pitch : i);
+    const int step = dir == 0 ? 1 : pitch;
+    int n = 0;
+    for (int x = 0; x < Nb; ++x) n += src[x * step] != 0;
+    cnt[dir][i] = n;
+  }
+  __syncthreads();
+  if (wave < n_dir) {                              // one wavefront per direction: exclusive scan
+    int32_t *ptr = (wave == 0 ? row_ptr : col_ptr) + (int64_t)slab * (Nb + 1);
+    int run = 0;
+    for (int x0 = 0; x0 < Nb; x0 += 64) {
+      const int x = x0 + lane;
+      const int v = x < Nb ? cnt[wave][x] : 0;
+      int inc = v;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+      }
+      if (x < Nb) {
+        cnt[wave][x] = run + inc - v;
+        if (part == 0) ptr[x] = run + inc - v;
+      }
+      run += __shfl(inc, 63, 64);
+    }
+    if (part == 0 && lane == 0) ptr[Nb] = run;
+  }
+  __syncthreads();
+  for (int item = part * 16 + wave; item < n_dir * Nb; item += 16 * kCsrParts) {
+    const int dir = item / Nb, i = item - dir * Nb;
+    int32_t *idx = (dir == 0 ? col_idx : row_idx) + (int64_t)slab * Nb * Nb;
+    int o = cnt[dir][i];
+    for (int x0 = 0; x0 < Nb; x0 += 64) {
+      const int x = x0 + lane;
+      const bool f = x < Nb && csr_smem[dir == 0 ? i * pitch + x : x * pitch + i] != 0;
+      const unsigned long long b = __ballot(f);
+      if (f) idx[o + __popcll(b & ((1ull << lane) - 1ull))] = x;
+      o += __popcll(b);
+    }
+  }
+}
+
 hipError_t launch_csr(const Problem &pb, const uint8_t *mask, int32_t *row_ptr, int32_t *col_idx,
                       int32_t *col_ptr, int32_t *row_idx, hipStream_t st) {
+  if (pb.Nb <= kCsrLdsMaxNb) {
+    const int lds = pb.Nb * (pb.Nb + 4);
+    hipError_t e0 = set_dynamic_lds_once(reinterpret_cast<const void *>(&csr_slab_kernel),
+                                         kCsrLdsMaxNb * (kCsrLdsMaxNb + 4));
+    if (e0 != hipSuccess) return e0;
+    hipLaunchKernelGGL(csr_slab_kernel, dim3(kCsrParts, pb.n_slabs), dim3(1024), lds, st, mask, pb.Nb, row_ptr,
+                       col_idx, col_ptr, row_idx);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(csr_count_kernel, dim3(pb.Nb, pb.n_slabs), dim3(128), 0, st, mask, pb.Nb,
                      row_ptr, col_ptr);
   hipError_t e = hipGetLastError();
