@@ -319,17 +319,28 @@ def main():
     # the dense backward (no index lists) and the mask build with seeded per-block sampling, a few
     # repetitions each
     dense_bwd_ms = None
+    bwd_plain_ms = None
     seeded_mask_ms = None
     try:
         if not args.no_dense_ref and not args.no_bwd:
             d_ev = [(ev(), ev()) for _ in range(3)]
             for a_ev, b_ev in d_ev:
                 a_ev.record(stream)
+                # (o_lo as in the timed steps, so that the two backward figures compare like with like)
                 binding.asa_attn_bwd(p, q, k, v, o, g, lse, None, None, None, None, dq, dk, dv, ws_bwd,
-                                     o_lo=None)
+                                     o_lo=o_lo)
                 b_ev.record(stream)
             torch.cuda.synchronize()
             dense_bwd_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[1:]]))
+            # the plain backward call (no saved low half of O: Delta by a walk over the tiles)
+            d_ev = [(ev(), ev()) for _ in range(5)]
+            for a_ev, b_ev in d_ev:
+                a_ev.record(stream)
+                binding.asa_attn_bwd(p, q, k, v, o, g, lse, bufs["row_ptr"], bufs["col_idx"],
+                                     bufs["col_ptr"], bufs["row_idx"], dq, dk, dv, ws_bwd, o_lo=None)
+                b_ev.record(stream)
+            torch.cuda.synchronize()
+            bwd_plain_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in d_ev[1:]]))
         if not args.no_sweep:
             ws_seed = binding.alloc_workspace(binding.asa_mask_seeded_workspace_bytes(p))
             bufs_r = binding.alloc_index_lists(p)
@@ -546,6 +557,7 @@ def main():
         "dense_fwd_tflops": None if dense_ms is None else round(
             p.B * p.H * p.Nb * p.Nb * tile_flops / (dense_ms * 1e-3) / 1e12, 2),
         "dense_bwd_ms": None if dense_bwd_ms is None else round(dense_bwd_ms, 4),
+        "bwd_without_o_lo_ms": None if bwd_plain_ms is None else round(bwd_plain_ms, 4),
         "seeded_sampling_mask_ms": None if seeded_mask_ms is None else round(seeded_mask_ms, 4),
         "kernel_speedup_vs_own_dense": None if dense_ms is None else round(
             dense_ms / float(np.median(mask_ms) + np.median(fwd_ms)), 3),

@@ -86,6 +86,7 @@ struct BwdArgs {
   int H, L, Lpad, Nb, n_slabs;
   float scale, scale_log2e;
   const int32_t *order;   // dK/dV: work item of each workgroup slot, longest column first inside an XCD's share (null: natural order)
+  const int32_t *order_q; // dQ: the same by rows
   // ---- global tokens of ASA_G (all zero / null when they are not used)
   // dK/dV kernels: the key side of a launch may be the pooled tokens instead of K, V
   int Lk, Nbk;            // valid key rows and key blocks of this launch (= L, Nb normally)
@@ -134,8 +135,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void dq_kernel(BwdArgs a) {
   constexpr int kStage = C::kDqStage;          // K rows [64][D], V rows [64][D] (t_swz images)
   constexpr int kVOff = C::kRowTile * 2;
 
-  const int work = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
-  if (work < 0) return;
+  const int slot = xcd_contiguous_work(blockIdx.x, a.n_slabs * a.Nb);
+  if (slot < 0) return;
+  const int work = a.order_q ? a.order_q[slot] : slot;
   const int slab = work / a.Nb;
   const int qb = work - slab * a.Nb;
   const int tid = threadIdx.x;
@@ -545,8 +547,8 @@ static size_t rowstat_bytes(const Problem &pb) {
 }
 size_t bwd_workspace_bytes(const Problem &pb) {
   // three [slab][Lpad] fp32 arrays (Delta, LSE in log2 units, the same minus the pooled keys'
-  // bias), then the order of the dK / dV workgroups
-  return 3 * rowstat_bytes(pb) + order_bytes(pb);
+  // bias), then the orders of the dK / dV and of the dQ workgroups
+  return 3 * rowstat_bytes(pb) + 2 * order_bytes(pb);
 }
 // sum of the per-range partial gradients of the pooled tokens into range 0's buffer
 __global__ void pooled_reduce_kernel(float *buf, int chunks, int64_t n) {
@@ -665,12 +667,17 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
   a.scale = pb.scale;
   a.scale_log2e = pb.scale * kLog2e;
   a.order = nullptr;
+  a.order_q = nullptr;
   {
     const int total = pb.n_slabs * pb.Nb;
     if (col_ptr && length_order_fits(total)) {
       e = launch_length_order(col_ptr, pb.Nb, total, order, st);
       if (e != hipSuccess) return e;
       a.order = order;
+      int32_t *order_q = reinterpret_cast<int32_t *>(ws + 3 * rb + order_bytes(pb));
+      e = launch_length_order(row_ptr, pb.Nb, total, order_q, st);
+      if (e != hipSuccess) return e;
+      a.order_q = order_q;
     }
   }
   a.Lk = pb.L; a.Nbk = pb.Nb;
@@ -688,6 +695,7 @@ hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const voi
     const float bias = pooled_bias;
     g = a;
     g.order = nullptr;
+    g.order_q = nullptr;
     g.k = gt->kg; g.v = gt->vg; g.tk = tvg; g.tv = tvg;
     g.col_ptr = nullptr; g.row_idx = nullptr;          // every query block attends the pooled tokens
     g.Lk = gt->Lg; g.Nbk = gt->Nbg; g.lse2 = lse2g;

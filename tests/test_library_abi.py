@@ -57,8 +57,8 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert L.asa_attn_bwd(ctypes.byref(p.c()), *([None] * 15), 0, None) == -1
     assert L.asa_build_mask(ctypes.byref(p.c()), *([None] * 9), 0, None) == -1
     assert L.asa_mask_from_scores(ctypes.byref(p.c()), None, None, None) == -1
-    # three fp32 row-statistics arrays [slab][Lpad] and the dK/dV workgroup order (256-byte granules)
-    assert L.asa_bwd_workspace_bytes(ctypes.byref(p.c())) == 3 * 2 * 1024 * 4 + 256
+    # three fp32 row-statistics arrays [slab][Lpad] and the two workgroup orders (256-byte granules)
+    assert L.asa_bwd_workspace_bytes(ctypes.byref(p.c())) == 3 * 2 * 1024 * 4 + 2 * 256
     # index lists: both (forward) / all four (backward) or none (dense); anything else is refused
     # before the pointers are looked at (the addresses below are never dereferenced)
     fake = ctypes.c_void_p(0x10000)
