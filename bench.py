@@ -260,6 +260,7 @@ def main():
     o_host = o.cpu() if not args.no_cpu_baseline else None    # the timed steps' O, for the oracle to check
 
     side_errors = {}   # a side measurement that fails must not take the headline line with it
+    tile_flops_const = 4.0 * 128 * 128 * 128
     # The same 25 % of the blocks chosen by the threshold itself: tau just below 1 and open
     # retention clamps, so that every row gets its own number of key blocks (Alg. 3 step 9) and
     # the forward meets rows of very different length (it takes them longest first).
@@ -411,6 +412,42 @@ def main():
             del sink, sk
     except Exception as exc:   # noqa: BLE001
         side_errors['measured_peaks'] = repr(exc)
+        torch.cuda.synchronize()
+
+    # How long ONE round of forward workgroups (64 tiles each, block 128, d 128) takes when a
+    # quarter, half or all of the 256 compute units hold a workgroup: the same work per workgroup,
+    # only the number of busy compute units differs.  A workgroup that runs faster on an emptier
+    # chip shows that the full-chip rate is set by something shared (power / clock), not by the
+    # kernel's schedule inside a compute unit.
+    occupancy = None
+    try:
+        if not args.no_sweep and (p.block, p.d) == (128, 128):
+            occupancy = []
+            for hh, ll in ((1, 8192), (1, 16384), (2, 16384), (12, 16384)):
+                nb = ll // 128
+                p_o = binding.Params(B=1, H=hh, L=ll, d=128, block=128, tau=0.9, r_min=64 / nb, r_max=64 / nb)
+                gen = torch.Generator(device="cuda").manual_seed(0)
+                tq, tk, tv = (torch.randn((1, hh, ll, 128), device="cuda", dtype=torch.float32,
+                                          generator=gen).to(torch.bfloat16) for _ in range(3))
+                b_o = binding.alloc_index_lists(p_o, with_csc=False)
+                wm = binding.alloc_workspace(binding.asa_mask_workspace_bytes(p_o))
+                wf = binding.alloc_workspace(binding.asa_fwd_workspace_bytes(p_o))
+                oo = torch.empty_like(tq)
+                ll_ = torch.empty((hh, ll), dtype=torch.float32, device="cuda")
+                binding.asa_build_mask(p_o, tq, tk, b_o["mask"], b_o["row_ptr"], b_o["col_idx"], None, None, None, wm)
+                o_ev = [(ev(), ev()) for _ in range(12)]
+                for a_ev, b_ev in o_ev:
+                    binding.asa_set_kernel_timing(a_ev, b_ev)
+                    binding.asa_attn_fwd(p_o, tq, tk, tv, b_o["row_ptr"], b_o["col_idx"], oo, ll_, wf)
+                torch.cuda.synchronize()
+                t_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in o_ev[3:]]))
+                wgs = hh * nb
+                occupancy.append({"workgroups": wgs, "rounds": -(-wgs // 256),
+                                  "us_per_round": round(t_ms * 1e3 / -(-wgs // 256), 1),
+                                  "tflops": round(wgs * 64 * tile_flops_const / (t_ms * 1e-3) / 1e12, 1)})
+                del tq, tk, tv, oo
+    except Exception as exc:   # noqa: BLE001
+        side_errors['occupancy'] = repr(exc)
         torch.cuda.synchronize()
 
     # density sweep (outside the timed steps): mask + forward at 10 / 25 / 50 / 100 % of the blocks
@@ -567,6 +604,7 @@ def main():
         "gilbert": gil,
         "density_sweep": sweep,
         "measured_peaks": measured,
+        "fwd_workgroup_round_vs_busy_compute_units": occupancy,
         "side_measurement_errors": side_errors or None,
         "roofline": {
             "kernel": (f"fwd_pp_kernel<{p.block},{p.d}>" if (p.block, p.d) == (128, 128)
