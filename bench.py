@@ -260,6 +260,7 @@ def main():
     o_host = o.cpu() if not args.no_cpu_baseline else None    # the timed steps' O, for the oracle to check
 
     side_errors = {}   # a side measurement that fails must not take the headline line with it
+    nnz_now = int(bufs["row_ptr"][:, -1].to(torch.int64).sum().item())
     tile_flops_const = 4.0 * 128 * 128 * 128
     # The same 25 % of the blocks chosen by the threshold itself: tau just below 1 and open
     # retention clamps, so that every row gets its own number of key blocks (Alg. 3 step 9) and
@@ -410,6 +411,22 @@ def main():
                         "mfma_only_frac_of_published_peak": round(flop / (mfma_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                         "note": "independent 32x32x16 bf16 MFMAs only, 16 wavefronts per CU, %.2f ms" % mfma_ms}
             del sink, sk
+            # fp32 atomic adds against plain stores in the pattern dQ would need if the backward
+            # walked the tiles once (5 tile products) and accumulated dQ with atomics
+            nqb = p.B * p.H * p.Nb
+            abuf = torch.zeros((nqb, 128 * 128), dtype=torch.float32, device="cuda")
+            for name, atomic in (("dq_pattern_plain_store_tbs", False), ("dq_pattern_fp32_atomic_add_tbs", True)):
+                a_evs = [(ev(), ev()) for _ in range(3)]
+                nbytes = 0.0
+                for a_ev, b_ev in a_evs:
+                    binding.asa_set_kernel_timing(a_ev, b_ev)
+                    nbytes = binding.asa_add_rate_probe(atomic, 3072, 16, nqb, abuf)
+                torch.cuda.synchronize()
+                t_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in a_evs[1:]]))
+                measured[name] = round(nbytes / (t_ms * 1e-3) / 1e12, 2)
+            measured["dq_by_atomics_would_take_ms"] = round(
+                nnz_now * 128 * 128 * 4 / (measured["dq_pattern_fp32_atomic_add_tbs"] * 1e12) * 1e3, 2)
+            del abuf
     except Exception as exc:   # noqa: BLE001
         side_errors['measured_peaks'] = repr(exc)
         torch.cuda.synchronize()

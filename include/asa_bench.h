@@ -29,8 +29,19 @@ int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, float *sink, double *
                         void *hip_stream);
 
 /*
+ * Calibration for benchmarks: the rate of fp32 atomic adds (atomic != 0) or of plain stores of
+ * the same bytes (atomic == 0) in the access pattern that a backward pass with a single walk over
+ * the tiles would need for dQ: `workgroups` workgroups each add `tiles_per_workgroup` tiles of
+ * 128 x 128 fp32 to pseudo-randomly chosen blocks of buf.
+ * buf: DEVICE, n_qblocks * 128 * 128 floats (read and written).  *bytes (HOST, optional) receives
+ * the payload bytes of the launch.  The profiling hook below brackets the kernel.
+ */
+int asa_add_rate_probe(int32_t atomic, int32_t workgroups, int32_t tiles_per_workgroup, int32_t n_qblocks,
+                       float *buf, double *bytes, void *hip_stream);
+
+/*
  * Profiling hook for benchmarks.  Arms the calling thread so that the NEXT asa_attn_fwd,
- * asa_attn_bwd, asa_build_mask, asa_reorder_tokens or asa_mfma_rate_probe call (of asa.h) records
+ * asa_attn_bwd, asa_build_mask, asa_reorder_tokens (asa.h) or probe call (this file) records
  * `start_event` immediately before and `stop_event` immediately after its dominant kernel(s) -- the tile loop of the forward, the
  * dK/dV and dQ kernels of the backward, the probe of the mask build -- on the call's stream,
  * leaving out the small preparation kernels around them.  Both are hipEvent_t handles owned by

@@ -42,7 +42,7 @@ EXPORTS = ["asa_version", "asa_error_string", "asa_last_hip_error", "asa_mask_wo
            "asa_fwd_g_workspace_bytes", "asa_attn_fwd_g", "asa_bwd_g_workspace_bytes",
            "asa_attn_bwd_g", "asa_mask_seeded_workspace_bytes", "asa_build_mask_seeded",
            "asa_sample_offsets", "asa_gilbert_order", "asa_reorder_tokens",
-           "asa_mfma_rate_probe", "asa_test_force_fwd_kernel"]
+           "asa_mfma_rate_probe", "asa_test_force_fwd_kernel", "asa_add_rate_probe"]
 
 
 def load():
@@ -72,6 +72,8 @@ def load():
     L.asa_attn_bwd_noalloc.argtypes = [pp] + [vp] * 15
     L.asa_attn_bwd_noalloc.restype = ctypes.c_int
     L.asa_set_kernel_timing.argtypes = [vp, vp]
+    L.asa_add_rate_probe.argtypes = [ctypes.c_int32] * 4 + [vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.asa_add_rate_probe.restype = ctypes.c_int
     L.asa_test_force_fwd_kernel.argtypes = [ctypes.c_int]
     L.asa_test_force_fwd_kernel.restype = ctypes.c_int
     for n in ("asa_global_token_count", "asa_fwd_g_workspace_bytes", "asa_bwd_g_workspace_bytes"):
@@ -202,6 +204,15 @@ def asa_attn_bwd(p: Params, q, k, v, o, d_o, lse, row_ptr, col_idx, col_ptr, row
                                _ptr(d_o), _ptr(lse), _ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr),
                                _ptr(row_idx), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                ws_bytes, _stream(stream)), "asa_attn_bwd")
+
+
+def asa_add_rate_probe(atomic: bool, workgroups: int, tiles_per_workgroup: int, n_qblocks: int, buf,
+                       stream=None) -> float:
+    """asa_bench.h: launches the calibration kernel; returns the payload bytes of the launch."""
+    b = ctypes.c_double()
+    _check(load().asa_add_rate_probe(int(bool(atomic)), workgroups, tiles_per_workgroup, n_qblocks,
+                                     _ptr(buf), ctypes.byref(b), _stream(stream)), "asa_add_rate_probe")
+    return b.value
 
 
 def asa_test_force_fwd_kernel(which: int):

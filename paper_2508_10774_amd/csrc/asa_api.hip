@@ -554,4 +554,14 @@ int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, float *sink, double *
   return finish(launch_mfma_rate(workgroups, iters, sink, reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
+int asa_add_rate_probe(int32_t atomic, int32_t workgroups, int32_t tiles_per_workgroup, int32_t n_qblocks,
+                       float *buf, double *bytes, void *hip_stream) {
+  if (workgroups < 1 || workgroups > 65535 || tiles_per_workgroup < 1 || tiles_per_workgroup > 4096 ||
+      n_qblocks < 1 || !buf || !aligned4(buf))
+    return ASA_ERR_INVALID_ARG;
+  if (bytes) *bytes = (double)workgroups * tiles_per_workgroup * 128.0 * 128.0 * 4.0;
+  return finish(launch_add_rate(atomic != 0, workgroups, tiles_per_workgroup, n_qblocks, buf,
+                                reinterpret_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

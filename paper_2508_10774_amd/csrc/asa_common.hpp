@@ -86,6 +86,7 @@ hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *s
                           const TensorView &ts, const TensorView &td, const int32_t *index,
                           hipStream_t st);
 hipError_t launch_mfma_rate(int grid, int iters, float *sink, hipStream_t st);
+hipError_t launch_add_rate(bool atomic, int grid, int tiles_per_wg, int n_qblocks, float *buf, hipStream_t st);
 hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st);
 size_t probe_workspace_bytes(const Problem &pb);
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);

@@ -298,4 +298,35 @@ hipError_t launch_mfma_rate(int grid, int iters, float *sink, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Calibration: fp32 atomic adds in the pattern that a backward with ONE pass over the tiles would
+// need for dQ (every workgroup adds 128 x 128 fp32 tiles to pseudo-randomly chosen query blocks
+// of a [n_qblocks][128][128] buffer, as the key blocks of a mask column do), or the same bytes
+// as plain stores.  The eight XCDs of the device have separate L2 caches, so device-scope atomics
+// are resolved beyond them; the rate this kernel reaches decides whether such a backward can pay.
+// ---------------------------------------------------------------------------------------
+template <bool ATOMIC>
+__global__ __launch_bounds__(256) void add_rate_kernel(float *buf, int tiles_per_wg, int n_qblocks) {
+  const int wg = blockIdx.x;
+  for (int t = 0; t < tiles_per_wg; ++t) {
+    unsigned h = (unsigned)(wg * 2654435761u) ^ (unsigned)(t * 40503u + 12345u);
+    h ^= h >> 13; h *= 0x5bd1e995u; h ^= h >> 15;
+    float *tile = buf + (size_t)(h % (unsigned)n_qblocks) * 128 * 128;
+    for (int e = threadIdx.x; e < 128 * 128; e += 256) {
+      const float v = 1.0f + (float)(e & 7);
+      if (ATOMIC) unsafeAtomicAdd(tile + e, v);     // the hardware's fp32 add, no compare-and-swap loop
+      else tile[e] = v;
+    }
+  }
+}
+
+hipError_t launch_add_rate(bool atomic, int grid, int tiles_per_wg, int n_qblocks, float *buf, hipStream_t st) {
+  timing_begin(st);
+  if (atomic) hipLaunchKernelGGL(add_rate_kernel<true>, dim3(grid), dim3(256), 0, st, buf, tiles_per_wg, n_qblocks);
+  else hipLaunchKernelGGL(add_rate_kernel<false>, dim3(grid), dim3(256), 0, st, buf, tiles_per_wg, n_qblocks);
+  hipError_t e = hipGetLastError();
+  timing_end(st);
+  return e;
+}
+
 }  // namespace asa
