@@ -46,7 +46,9 @@ typedef enum asa_status {
  * Problem description shared by all entry points.
  *
  * Supported: d in {64, 128}; block in {64, 128}; 1 <= L; Nb = ceil(L/block) <= 1024;
- * 1 <= k_samples <= 16 and k_samples <= block.
+ * 1 <= k_samples <= 16, or k_samples == block: every token sampled, the exact importance map
+ * that Sec. 3.3 Step 1 defines and the sampling approximates (mask generation then costs as
+ * much as dense attention scores and takes L <= 16 384).
  */
 typedef struct asa_params {
   int32_t B, H, L, d;

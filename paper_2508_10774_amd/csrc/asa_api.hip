@@ -79,13 +79,17 @@ int resolve(const asa_params *p, Problem *o) {
   o->n_slabs = p->B * p->H;
   // sampling (Alg. 2 steps 1-3): k offsets inside a block, shared by every block
   if (p->k_samples < 1 || p->k_samples > p->block) return ASA_ERR_INVALID_ARG;
-  if (p->k_samples > kMaxSamples) return ASA_ERR_UNSUPPORTED;
+  // up to 16 samples per block (the probe's MFMA tile is 2 blocks x 16 samples), or all of them
+  o->every_token = p->k_samples == p->block && p->k_samples > kMaxSamples;
+  if (p->k_samples > kMaxSamples && !o->every_token) return ASA_ERR_UNSUPPORTED;
   o->ks = p->k_samples;
+  int prev = -1;
   for (int u = 0; u < o->ks; ++u) {
     int off = p->sample_offsets ? p->sample_offsets[u] : u * (p->block / p->k_samples);
     if (off < 0 || off >= p->block) return ASA_ERR_INVALID_ARG;
-    if (u && off <= o->offs[u - 1]) return ASA_ERR_INVALID_ARG;
-    o->offs[u] = off;
+    if (off <= prev) return ASA_ERR_INVALID_ARG;
+    prev = off;
+    if (u < kMaxSamples) o->offs[u] = off;   // (k = block leaves no choice: the offsets are 0 .. block - 1)
   }
   // rule parameters (Alg. 3 step 9)
   if (p->tau != p->tau) return ASA_ERR_INVALID_ARG;
@@ -158,9 +162,31 @@ int asa_set_kernel_timing(void *start_event, void *stop_event) {
   return ASA_OK;
 }
 
+// Every token sampled (k = block): the probe runs on blocks of 16 tokens (its own tile size,
+// offsets 0..15) and the map of the real blocks is the (block / 16)^2 max-pool of that map.
+static Problem fine_problem(const Problem &pb) {
+  Problem f = pb;
+  f.block = kMaxSamples;
+  f.Nb = (pb.L + kMaxSamples - 1) / kMaxSamples;
+  f.Lpad = f.Nb * kMaxSamples;
+  f.ks = kMaxSamples;
+  f.every_token = false;
+  for (int u = 0; u < kMaxSamples; ++u) f.offs[u] = u;
+  return f;
+}
+static size_t scores_bytes(const Problem &pb) {
+  return round256((size_t)pb.n_slabs * pb.Nb * pb.Nb * sizeof(float));
+}
+
 size_t asa_mask_workspace_bytes(const asa_params *p) {
   Problem pb;
   if (resolve(p, &pb) != ASA_OK) return 0;
+  if (pb.every_token) {
+    const Problem f = fine_problem(pb);
+    if (f.Nb > kMaxNb) return 0;
+    // the probe's workspace on the fine blocks, the fine map, the pooled map
+    return round256(probe_workspace_bytes(f)) + scores_bytes(f) + scores_bytes(pb);
+  }
   // the probe's per-row block maxima and soft-max statistics
   return round256(probe_workspace_bytes(pb));
 }
@@ -198,11 +224,29 @@ static int build_mask_impl(const asa_params *p, const uint64_t *seed, const void
   if (!aligned16(q) || !aligned16(k) || !aligned4(row_ptr) || !aligned4(col_idx) ||
       !aligned4(col_ptr) || !aligned4(row_idx) || !aligned4(p_imp))
     return ASA_ERR_INVALID_ARG;
+  if (pb.every_token && fine_problem(pb).Nb > kMaxNb) return ASA_ERR_UNSUPPORTED;   // L <= 16 * 1024 there
   const size_t base = asa_mask_workspace_bytes(p);
   if (!workspace || workspace_bytes < base + (seed ? table_bytes(pb) : 0) || !aligned16(workspace))
     return ASA_ERR_WORKSPACE;
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  if (pb.every_token) {
+    // (a seed changes nothing here: every position of every block is in the sample)
+    const Problem f = fine_problem(pb);
+    float *fine = reinterpret_cast<float *>(ws + round256(probe_workspace_bytes(f)));
+    float *scores = p_imp ? p_imp : reinterpret_cast<float *>(ws + round256(probe_workspace_bytes(f)) + scores_bytes(f));
+    timing_begin(st);
+    hipError_t e = launch_probe(f, q, k, workspace, st, nullptr);
+    timing_end(st);
+    if (e != hipSuccess) return finish(e);
+    e = launch_finish_rule(f, workspace, fine, nullptr, nullptr, st);   // the fine map only, no rule
+    if (e != hipSuccess) return finish(e);
+    e = launch_pool_scores(fine, f.Nb, scores, pb.Nb, pb.block / kMaxSamples, pb.n_slabs, st);
+    if (e != hipSuccess) return finish(e);
+    e = launch_rule(pb, scores, mask, st);
+    if (e != hipSuccess) return finish(e);
+    return finish(launch_csr(pb, mask, row_ptr, col_idx, col_ptr, row_idx, st));
+  }
   uint8_t *table = nullptr;
   if (seed) {
     table = ws + base;

@@ -34,6 +34,7 @@ struct Problem {
   int Lpad;      // Nb * block
   int n_slabs;   // B * H
   int ks;        // samples per block
+  bool every_token;  // ks == block > kMaxSamples: every token is sampled (the exact map of Sec. 3.3 Step 1)
   int n_prefix_blocks;
   int m_min, m_max;
   float tau;
@@ -90,6 +91,10 @@ hipError_t launch_add_rate(bool atomic, int grid, int tiles_per_wg, int n_qblock
 hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st);
 size_t probe_workspace_bytes(const Problem &pb);
 hipError_t launch_rule(const Problem &pb, const float *scores, uint8_t *mask, hipStream_t st);
+// dst[s][i][j] = max over the g x g block of src[s][i*g .. ][j*g .. ] (src rows/columns past n_src
+// do not exist): the importance map of blocks of g * 16 tokens from the map of 16-token blocks
+hipError_t launch_pool_scores(const float *src, int n_src, float *dst, int n_dst, int g, int n_slabs,
+                              hipStream_t st);
 hipError_t launch_bwd(const Problem &pb, const void *q, const void *k, const void *v,
                       const void *o, const void *o_lo, const void *d_o, const float *lse,
                       const int32_t *row_ptr,

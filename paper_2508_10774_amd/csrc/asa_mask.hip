@@ -606,8 +606,27 @@ __global__ __launch_bounds__(256) void finish_rule_kernel(ProbeArgs a, RuleArgs 
       key[r] = ((unsigned long long)desc_key(best) << 32) | (unsigned)j;
     }
   }
+  if (ra.mask == nullptr) return;   // the caller only wanted the map (wave-uniform)
   rule_on_keys<NPAD>(key, cum_all[wave], lane, i, a.Nb, ra.tau, ra.m_min, ra.m_max, ra.n_prefix_blocks,
                      ra.mask + (int64_t)row * a.Nb);
+}
+
+// dst[s][i][j] = max of src[s][i g .. i g + g)[j g .. j g + g) (clipped at n_src): the importance
+// map of blocks that are g times as large.  One thread per output element.
+__global__ void pool_scores_kernel(const float *src, int n_src, float *dst, int n_dst, int g) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x, i = blockIdx.y, s = blockIdx.z;
+  if (j >= n_dst) return;
+  const float *in = src + (int64_t)s * n_src * n_src;
+  float best = 0.f;
+  for (int a = i * g; a < min(n_src, i * g + g); ++a)
+    for (int b = j * g; b < min(n_src, j * g + g); ++b) best = fmaxf(best, in[(int64_t)a * n_src + b]);
+  dst[((int64_t)s * n_dst + i) * n_dst + j] = best;
+}
+hipError_t launch_pool_scores(const float *src, int n_src, float *dst, int n_dst, int g, int n_slabs,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(pool_scores_kernel, dim3((n_dst + 63) / 64, n_dst, n_slabs), dim3(64), 0, st, src,
+                     n_src, dst, n_dst, g);
+  return hipGetLastError();
 }
 
 hipError_t launch_finish_rule(const Problem &pb, void *workspace, float *p_imp, uint8_t *mask,

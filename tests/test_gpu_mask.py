@@ -217,3 +217,38 @@ def test_build_mask_without_p_imp_uses_workspace_and_is_deterministic():
     with pytest.raises(binding.AsaError, match="workspace"):
         binding.asa_build_mask(p, util.dev_bf16(qb), util.dev_bf16(kb), bufs["mask"],
                                bufs["row_ptr"], bufs["col_idx"])
+
+
+@pytest.mark.parametrize("B,H,L,d,block", [(1, 2, 1024, 64, 64), (1, 2, 1000, 128, 128),
+                                            (2, 1, 333, 64, 128), (1, 1, 16384, 64, 64)])
+def test_every_token_sampled_gives_the_exact_importance_map(B, H, L, d, block):
+    """k = block: no sampling at all, the conceptual definition of Sec. 3.3 Step 1 (soft-max over
+    all keys, max-pooled over blocks).  The library computes it on 16-token blocks and max-pools;
+    the oracle is its ordinary probe with every offset listed (pinned against the dense soft-max
+    in tests/test_oracle_mask.py)."""
+    print(f"case B={B} H={H} L={L} d={d} block={block} k={block}", flush=True)
+    heads = H if L < 4000 else 1
+    qb, kb = (synth.make_iid((B, H, L, d), L + block, s) for s in range(2))
+    if L == 1024:
+        w = synth.TINY
+        qb, kb, _ = synth.make_qkv(w, seed=3)          # video-like, peaked scores
+    p = binding.Params(B=B, H=H, L=L, d=d, block=block, k_samples=block, tau=0.9)
+    _check_build(p, qb, kb, np.arange(block, dtype=np.int32), f"k=b L={L} block={block}")
+    # the seeded build draws "all of them" too
+    bufs = binding.alloc_index_lists(p, with_csc=False)
+    bufs2 = binding.alloc_index_lists(p, with_csc=False)
+    ws = binding.alloc_workspace(binding.asa_mask_seeded_workspace_bytes(p))
+    q, k = util.dev_bf16(qb), util.dev_bf16(kb)
+    binding.asa_build_mask(p, q, k, bufs["mask"], bufs["row_ptr"], bufs["col_idx"], None, None, None, ws)
+    binding.asa_build_mask_seeded(p, 99, q, k, bufs2["mask"], bufs2["row_ptr"], bufs2["col_idx"], None,
+                                  None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(bufs["mask"], bufs2["mask"])
+    del heads
+
+
+def test_every_token_sampled_is_refused_beyond_its_length_limit():
+    p = binding.Params(B=1, H=1, L=16385, d=64, block=64, k_samples=64)
+    assert binding.asa_mask_workspace_bytes(p) == 0
+    p17 = binding.Params(B=1, H=1, L=4096, d=64, block=64, k_samples=17)     # neither <= 16 nor all
+    assert binding.asa_mask_workspace_bytes(p17) == 0
