@@ -410,6 +410,29 @@ def main():
                         "mfma_only_shader_clock_ghz": round(float(np.median(sk[:, 0] / sk[:, 1])) * 0.1, 3),
                         "mfma_only_frac_of_published_peak": round(flop / (mfma_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                         "note": "independent 32x32x16 bf16 MFMAs only, 16 wavefronts per CU, %.2f ms" % mfma_ms}
+            # the same MFMA stream at lower duty cycles of the matrix pipes (one MFMA wavefront per
+            # SIMD, one workgroup per CU, a pause behind every 16 MFMAs), alone and beside a
+            # wavefront of exponentials and multiply-adds: the clock that the power limit leaves in
+            # each case, i.e. how much of a denser matrix schedule the device takes back
+            duty = []
+            n_it = 65536
+            for idle, vec in ((1, False), (3, False), (7, False), (1, True), (3, True), (7, True)):
+                d_ev = [(ev(), ev()) for _ in range(3)]
+                for a_ev, b_ev in d_ev:
+                    binding.asa_set_kernel_timing(a_ev, b_ev)
+                    flop = binding.asa_mfma_rate_probe(256, n_it, sink, idle_sleep=idle, vector_stream=vec)
+                torch.cuda.synchronize()
+                d_ms = d_ev[-1][0].elapsed_time(d_ev[-1][1])
+                sk = sink.view(512, 512)[:256].double().cpu().numpy()
+                row = {"idle_sleep": idle, "vector_stream": vec,
+                       "matrix_busy": round(float(np.median(4 * n_it * 32 / sk[:, 0])), 3),
+                       "shader_clock_ghz": round(float(np.median(sk[:, 0] / sk[:, 1])) * 0.1, 3),
+                       "tflops": round(flop / (d_ms * 1e-3) / 1e12, 1),
+                       "frac_of_published_peak": round(flop / (d_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 3)}
+                if vec:   # blocks of 16 exponentials + 96 other vector instructions per 16 MFMAs
+                    row["vector_blocks_per_16_mfma"] = round(float(np.median(sk[:, 256])) / (n_it / 4), 2)
+                duty.append(row)
+            measured["mfma_duty_cycle"] = duty
             del sink, sk
             # fp32 atomic adds against plain stores in the pattern dQ would need if the backward
             # walked the tiles once (5 tile products) and accumulated dQ with atomics

@@ -19,14 +19,19 @@ extern "C" {
  * matrix cores sustain on the device at hand next to the published peak that the roofline uses.
  * The operands are pseudo-random and differ between consecutive MFMAs (with identical operands
  * far fewer gates switch and the clock runs higher than in any real kernel).
+ * idle_sleep (0..7) and vector_stream (0 / 1) vary the load to show how the device's power limit
+ * answers: with idle_sleep > 0 only 4 wavefronts per workgroup (one per SIMD) issue MFMAs and
+ * each pauses for `s_sleep idle_sleep` behind every 16 of them (a duty cycle below 1 when one
+ * workgroup runs per compute unit); with vector_stream the other 4 wavefronts run exponentials
+ * and multiply-adds beside them until the MFMA loops end.  In both cases 4 wavefronts count in *flop.
  * sink: DEVICE, workgroups * 512 floats (written).  Of every workgroup's 512, element 0 holds the
  * shader-clock cycles of its first wavefront's MFMA loop and element 1 the same interval in
  * ticks of the constant 100 MHz clock (their ratio is the shader clock under this load); the
  * rest is meaningless.  *flop (HOST, optional) receives the floating-point operations of the
  * launch.  The profiling hook below brackets it.  Returns an asa_status (asa.h).
  */
-int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, float *sink, double *flop,
-                        void *hip_stream);
+int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, int32_t idle_sleep, int32_t vector_stream,
+                        float *sink, double *flop, void *hip_stream);
 
 /*
  * Calibration for benchmarks: the rate of fp32 atomic adds (atomic != 0) or of plain stores of

@@ -82,7 +82,8 @@ def load():
     L.asa_global_tokens.argtypes = [pp, ctypes.c_int, vp, vp, vp, vp, vp]
     L.asa_attn_fwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 11 + [ctypes.c_size_t, vp]
     L.asa_attn_bwd_g.argtypes = [pp, ctypes.c_int] + [vp] * 17 + [ctypes.c_size_t, vp]
-    L.asa_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.asa_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp,
+                                      ctypes.POINTER(ctypes.c_double), vp]
     L.asa_mfma_rate_probe.restype = ctypes.c_int
     L.asa_gilbert_order.argtypes = [ctypes.c_int32] * 4 + [vp, vp]
     L.asa_reorder_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
@@ -308,11 +309,12 @@ def asa_reorder_tokens(p: Params, src, dst, index, src_stride=None, dst_stride=N
                                      _stream(stream)), "asa_reorder_tokens")
 
 
-def asa_mfma_rate_probe(workgroups: int, iters: int, sink, stream=None) -> float:
+def asa_mfma_rate_probe(workgroups: int, iters: int, sink, idle_sleep: int = 0, vector_stream: bool = False,
+                        stream=None) -> float:
     """Launch the MFMA-only calibration kernel; returns the FLOP of the launch."""
     flop = ctypes.c_double(0.0)
-    _check(load().asa_mfma_rate_probe(workgroups, iters, _ptr(sink), ctypes.byref(flop), _stream(stream)),
-           "asa_mfma_rate_probe")
+    _check(load().asa_mfma_rate_probe(workgroups, iters, idle_sleep, int(vector_stream), _ptr(sink),
+                                      ctypes.byref(flop), _stream(stream)), "asa_mfma_rate_probe")
     return flop.value
 
 

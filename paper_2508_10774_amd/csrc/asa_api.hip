@@ -590,12 +590,15 @@ int asa_reorder_tokens(const asa_params *p, int32_t n_tensors, const void *const
                                reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
-int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, float *sink, double *flop,
-                        void *hip_stream) {
-  if (workgroups < 1 || workgroups > 65535 || iters < 1 || iters > (1 << 24) || !sink || !aligned4(sink))
+int asa_mfma_rate_probe(int32_t workgroups, int32_t iters, int32_t idle_sleep, int32_t vector_stream,
+                        float *sink, double *flop, void *hip_stream) {
+  if (workgroups < 1 || workgroups > 65535 || iters < 1 || iters > (1 << 24) || idle_sleep < 0 ||
+      idle_sleep > 7 || !sink || !aligned4(sink))
     return ASA_ERR_INVALID_ARG;
-  if (flop) *flop = (double)workgroups * 8.0 * 4.0 * (double)iters * (2.0 * 32 * 32 * 16);
-  return finish(launch_mfma_rate(workgroups, iters, sink, reinterpret_cast<hipStream_t>(hip_stream)));
+  const double matrix_waves = (idle_sleep > 0 || vector_stream) ? 4.0 : 8.0;
+  if (flop) *flop = (double)workgroups * matrix_waves * 4.0 * (double)iters * (2.0 * 32 * 32 * 16);
+  return finish(launch_mfma_rate(workgroups, iters, idle_sleep, vector_stream != 0, sink,
+                                 reinterpret_cast<hipStream_t>(hip_stream)));
 }
 
 int asa_add_rate_probe(int32_t atomic, int32_t workgroups, int32_t tiles_per_workgroup, int32_t n_qblocks,

@@ -86,7 +86,7 @@ int gilbert_order(int T, int Y, int X, int n_prefix, int32_t *order, int32_t *in
 hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *src, void *const *dst,
                           const TensorView &ts, const TensorView &td, const int32_t *index,
                           hipStream_t st);
-hipError_t launch_mfma_rate(int grid, int iters, float *sink, hipStream_t st);
+hipError_t launch_mfma_rate(int grid, int iters, int idle_sleep, bool vector_stream, float *sink, hipStream_t st);
 hipError_t launch_add_rate(bool atomic, int grid, int tiles_per_wg, int n_qblocks, float *buf, hipStream_t st);
 hipError_t launch_sample_offsets(const Problem &pb, uint64_t seed, uint8_t *table, hipStream_t st);
 size_t probe_workspace_bytes(const Problem &pb);

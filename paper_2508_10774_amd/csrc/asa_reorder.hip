@@ -250,12 +250,55 @@ hipError_t launch_reorder(const Problem &pb, int n_tensors, const void *const *s
 }
 
 // ---------------------------------------------------------------------------------------
-// Calibration kernel for benchmarks: nothing but independent 32x32x16 bf16 MFMAs, 8 wavefronts
-// per CU on every CU, so that a report can put the rate the matrix cores sustain on this
-// device and at its clocks next to the published peak.  16 accumulators per wavefront are
-// four independent chains; results are stored so that nothing is optimised away.
+// Calibration kernel for benchmarks: nothing but independent 32x32x16 bf16 MFMAs, so that a
+// report can put the rate the matrix cores sustain on this device and at its clocks next to the
+// published peak.  16 accumulators per wavefront are four independent chains; results are
+// stored so that nothing is optimised away.
+// SLEEP = 0, VEC = false: all 8 wavefronts of a workgroup run the MFMA loop (two per SIMD).
+// SLEEP > 0: only wavefronts 0..3 do (one per SIMD) and pause for s_sleep SLEEP behind every 16
+// MFMAs, which sets the duty cycle of the matrix pipes; the others leave at once.
+// VEC: wavefronts 4..7 run a stream of exponentials and multiply-adds beside the MFMA loop of
+// wavefronts 0..3 (at the higher priority, as in the attention kernels) until those have finished.
+// What the shader clock does in each case shows how far the device's power limit takes back what
+// a denser schedule of the matrix pipes gains.
 // ---------------------------------------------------------------------------------------
+template <int SLEEP, bool VEC>
 __global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, float *sink) {
+  __shared__ volatile int finished;   // matrix wavefronts that have left their loop (VEC only)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (VEC) {
+    if (threadIdx.x == 0) finished = 0;
+    __syncthreads();
+  }
+  if ((SLEEP > 0 || VEC) && wave >= 4) {
+    float r = 0.f;
+    if (VEC) {
+      __builtin_amdgcn_s_setprio(3);
+      float x[16];
+      int blocks = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = 0.5f + (float)(threadIdx.x & 63) * 0.001f + (float)i * 0.01f;
+      // at most one block of arithmetic per 4 MFMAs of the matrix wavefronts: the loop ends with
+      // theirs (looked up every eighth block), or by its own count if they are somehow slower
+      for (int it = 0; it < iters; it += 8) {
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 0.999f, -0.3f));
+            r += e;
+            x[i] = __builtin_fmaf(fmaxf(__builtin_fmaf(e, 0.5f, 0.1f), x[(i + 1) & 15] * 0.97f), 0.99f, 0.002f);
+          }
+        }
+        blocks += 8;
+        if (finished >= 4) break;
+      }
+      r += x[3];
+      if (threadIdx.x == 256) r = (float)blocks;   // how far the stream got beside the MFMA loops
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
+    return;
+  }
+  if (VEC) __builtin_amdgcn_s_setprio(0);
   // four different operand pairs of pseudo-random bf16 values in [-1, 1): consecutive MFMAs see
   // different data, as they do in a real kernel (identical operands switch far fewer gates and
   // let the clock run higher than any real kernel's)
@@ -279,8 +322,10 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, float *sink) 
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c], b[c], acc[c], 0, 0, 0);
+    if (SLEEP > 0 && (it & 3) == 3) __builtin_amdgcn_s_sleep(SLEEP);
   }
   const long long t1 = clock64(), w1 = wall_clock64();
+  if (VEC && (threadIdx.x & 63) == 0) atomicAdd(const_cast<int *>(&finished), 1);
   float r = 0.f;
 #pragma unroll
   for (int c = 0; c < 4; ++c) r += acc[c][0] + acc[c][15];
@@ -290,10 +335,21 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, float *sink) 
   sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
-// launches grid x 512 threads, each wavefront issuing 4 * iters MFMAs of 2 * 32 * 32 * 16 FLOP
-hipError_t launch_mfma_rate(int grid, int iters, float *sink, hipStream_t st) {
+// launches grid x 512 threads; each wavefront that runs the MFMA loop issues 4 * iters MFMAs of
+// 2 * 32 * 32 * 16 FLOP.  idle_sleep in 0..7 (the argument of s_sleep behind every 16 MFMAs).
+hipError_t launch_mfma_rate(int grid, int iters, int idle_sleep, bool vector_stream, float *sink, hipStream_t st) {
   timing_begin(st);
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(512), 0, st, iters, sink);
+#define ASA_RATE_CASE(S)                                                                                     \
+  case S:                                                                                                    \
+    if (vector_stream) hipLaunchKernelGGL((mfma_rate_kernel<S, true>), dim3(grid), dim3(512), 0, st, iters, sink); \
+    else hipLaunchKernelGGL((mfma_rate_kernel<S, false>), dim3(grid), dim3(512), 0, st, iters, sink);        \
+    break;
+  switch (idle_sleep) {
+    ASA_RATE_CASE(0) ASA_RATE_CASE(1) ASA_RATE_CASE(2) ASA_RATE_CASE(3)
+    ASA_RATE_CASE(4) ASA_RATE_CASE(5) ASA_RATE_CASE(6) ASA_RATE_CASE(7)
+    default: timing_end(st); return hipErrorInvalidValue;
+  }
+#undef ASA_RATE_CASE
   timing_end(st);
   return hipGetLastError();
 }

@@ -91,7 +91,8 @@ int main() {
     EXPECT(asa_reorder_tokens(&p, 1, src, dst, nullptr, nullptr, fi, nullptr) == ASA_ERR_INVALID_ARG);  // in place
     EXPECT(asa_reorder_tokens(&p, 4, src, dst, nullptr, nullptr, fi, nullptr) == ASA_ERR_INVALID_ARG);
   }
-  EXPECT(asa_mfma_rate_probe(0, 1, ff, nullptr, nullptr) == ASA_ERR_INVALID_ARG);
+  EXPECT(asa_mfma_rate_probe(0, 1, 0, 0, ff, nullptr, nullptr) == ASA_ERR_INVALID_ARG);
+  EXPECT(asa_mfma_rate_probe(1, 1, 8, 0, ff, nullptr, nullptr) == ASA_ERR_INVALID_ARG);
   EXPECT(asa_add_rate_probe(1, 0, 1, 1, ff, nullptr, nullptr) == ASA_ERR_INVALID_ARG);
   EXPECT(asa_set_kernel_timing(fake, nullptr) == ASA_ERR_INVALID_ARG);
   EXPECT(asa_set_kernel_timing(nullptr, nullptr) == ASA_OK);

@@ -129,6 +129,14 @@ def test_mfma_rate_probe_runs_and_checks_its_arguments():
     torch.cuda.synchronize()
     assert flop == 4 * 8 * 4 * 8 * 2 * 32 * 32 * 16
     assert torch.isfinite(sink).all()
+    # with idle pauses or a vector stream beside it, four wavefronts per workgroup count
+    for kw in ({"idle_sleep": 3}, {"vector_stream": True}, {"idle_sleep": 7, "vector_stream": True}):
+        flop = binding.asa_mfma_rate_probe(4, 8, sink, **kw)
+        torch.cuda.synchronize()
+        assert flop == 4 * 4 * 4 * 8 * 2 * 32 * 32 * 16
+        assert torch.isfinite(sink).all()
+    with pytest.raises(binding.AsaError):
+        binding.asa_mfma_rate_probe(4, 8, sink, idle_sleep=8)
     with pytest.raises(binding.AsaError):
         binding.asa_mfma_rate_probe(0, 8, sink)
     with pytest.raises(binding.AsaError):
