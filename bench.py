@@ -433,6 +433,20 @@ def main():
                     row["vector_blocks_per_16_mfma"] = round(float(np.median(sk[:, 256])) / (n_it / 4), 2)
                 duty.append(row)
             measured["mfma_duty_cycle"] = duty
+            # what the memory system sustains for a plain copy: Q, K, V gathered by the identity
+            # order (every row read once and written once by the library's gather kernel)
+            ident = torch.arange(p.L, dtype=torch.int32, device="cuda")
+            c_dst = [torch.empty_like(q) for _ in range(3)]
+            c_ev = [(ev(), ev()) for _ in range(5)]
+            for a_ev, b_ev in c_ev:
+                binding.asa_set_kernel_timing(a_ev, b_ev)
+                binding.asa_reorder_tokens(p, [q, k, v], c_dst, ident)
+            torch.cuda.synchronize()
+            c_ms = float(np.median([a_ev.elapsed_time(b_ev) for a_ev, b_ev in c_ev[1:]]))
+            c_bytes = 3 * p.B * p.H * p.L * p.d * 2 * 2
+            measured["hbm_copy_tbs"] = round(c_bytes / (c_ms * 1e-3) / 1e12, 2)
+            measured["hbm_copy_frac_of_published_peak"] = round(c_bytes / (c_ms * 1e-3) / 1e12 / 8.0, 3)
+            del c_dst, ident
             del sink, sk
             # fp32 atomic adds against plain stores in the pattern dQ would need if the backward
             # walked the tiles once (5 tile products) and accumulated dQ with atomics
