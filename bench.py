@@ -706,6 +706,13 @@ def cog_point(args, binding, synth, torch, measure_point, dev):
     r["setting"] = (f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} block={w.block}, tau=0.9, "
                     f"r_min=r_max={dens} (fixed budget) + {w.n_text} always-kept text tokens, seed={args.seed}")
     r["kernel"] = f"fwd_kernel<{w.block},{w.d}>"
+    # At d = 64 the forward is bound by the vector ALU: per 64-key step a wavefront needs 16 MFMAs
+    # (512 matrix-pipe cycles) and 32 quarter-rate exponentials + 96 full-rate vector instructions
+    # (896 cycles) + 16 MFMA issue slots (64): the soft-max caps the matrix duty at 512 / 960.
+    alu_cap = 512.0 / 960.0
+    r["bound"] = "alu"
+    r["alu_cap_of_matrix_duty"] = round(alu_cap, 3)
+    r["fwd_kernel_frac_of_alu_capped_peak"] = round(r["fwd_kernel_frac_of_bf16_peak"] / alu_cap, 4)
     if not args.no_cpu_baseline:
         heads = [0, w.H // 2, w.H - 1]
         offs = synth.default_sample_offsets(w.block, w.k_samples)
